@@ -1,0 +1,192 @@
+/*
+ * CPU oracle, part 2: the arithmetic of the update stage.
+ *
+ * TEST INFRASTRUCTURE ONLY - never linked into, loaded by or called from the
+ * product library.  Plain loops, one element at a time, no blocking or fusion
+ * beyond what each definition states.  Build: gcc -O2 -fno-fast-math
+ * -ffp-contract=off (so no multiply-add is ever fused) -fopenmp.  OpenMP only
+ * splits the element range; the operations applied to one element, and their
+ * order, do not depend on the thread count.
+ *
+ * What is computed (paper Sec. 3.2, update stage of PaRO-IGG / IIG / NIG:
+ * "each GPU uses its gradient shard to update the optimizer state it keeps and
+ * produces low-precision parameters"; Sec. 3.1.2: 2 bytes/param gradients and
+ * parameters, 12 bytes/param of Adam state = fp32 master copy + two moments):
+ *
+ *   fold   g[e]  = sum over the P ranks' contributions, added in the order the
+ *                  reduce-scatter ring delivers them (Sec. 3.4), in fp32;
+ *   sumsq  S     = sum_e g[e]^2 in fp64;
+ *   clip   coef  = min(1, max_norm / (grad_scale * sqrt(S_total) + 1e-6));
+ *                  not in the paper - the convention of the usual global-norm
+ *                  clipping routine;  PARITY UNPINNED by the paper, pinned to
+ *                  torch.nn.utils.clip_grad_norm_ in the tests;
+ *   adam   Adam (Kingma & Ba, Algorithm 1) with bias correction, decoupled
+ *          weight decay by default, classic L2 as an option;
+ *   pack   bf16 round-to-nearest-even of the updated master parameter.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static inline float bf16_to_f32(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;          /* bf16 is the top half of an fp32: exact */
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* ---- fold ----------------------------------------------------------------
+ * src[k], k = 0..P-1, are the contributions ALREADY LISTED IN FOLD ORDER.
+ * Consecutive runs of group_len sources are added left to right into a group
+ * partial A; the partials are added left to right into X.  group_len == P is
+ * the flat ring.  No add with a zero start value is made (it would turn -0
+ * into +0). */
+void orc_fold_bf16(const uint16_t *const *src, int P, int group_len, int64_t n, float *out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < n; e++) {
+        float X = 0.0f;
+        for (int k0 = 0; k0 < P; k0 += group_len) {
+            float A = bf16_to_f32(src[k0][e]);
+            for (int l = 1; l < group_len; l++) A = A + bf16_to_f32(src[k0 + l][e]);
+            X = (k0 == 0) ? A : X + A;
+        }
+        out[e] = X;
+    }
+}
+
+void orc_fold_f32(const float *const *src, int P, int group_len, int64_t n, float *out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < n; e++) {
+        float X = 0.0f;
+        for (int k0 = 0; k0 < P; k0 += group_len) {
+            float A = src[k0][e];
+            for (int l = 1; l < group_len; l++) A = A + src[k0 + l][e];
+            X = (k0 == 0) ? A : X + A;
+        }
+        out[e] = X;
+    }
+}
+
+/* ---- sum of squares --------------------------------------------------------
+ * fp64; each square of an fp32 value is exact in fp64.  Elements are summed in
+ * index order inside blocks of 65536, block sums in block order. */
+#define ORC_BLOCK 65536
+double orc_sumsq(const float *g, int64_t n) {
+    int64_t nb = (n + ORC_BLOCK - 1) / ORC_BLOCK;
+    if (nb <= 0) return 0.0;
+    double *part = (double *)malloc((size_t)nb * sizeof(double));
+    if (!part) return NAN;
+#pragma omp parallel for schedule(static)
+    for (int64_t b = 0; b < nb; b++) {
+        int64_t lo = b * ORC_BLOCK, hi = lo + ORC_BLOCK < n ? lo + ORC_BLOCK : n;
+        double s = 0.0;
+        for (int64_t e = lo; e < hi; e++) s += (double)g[e] * (double)g[e];
+        part[b] = s;
+    }
+    double tot = 0.0;
+    for (int64_t b = 0; b < nb; b++) tot += part[b];
+    free(part);
+    return tot;
+}
+
+/* ---- clip coefficient ------------------------------------------------------ */
+double orc_clip_coef(double total_sumsq, float grad_scale, float max_norm) {
+    if (!(max_norm > 0.0f)) return 1.0;
+    double norm = (double)grad_scale * sqrt(total_sumsq);
+    double c = (double)max_norm / (norm + 1e-6);
+    return c < 1.0 ? c : 1.0;
+}
+
+/* ---- Adam, reference: fp64 arithmetic on the fp32 inputs, rounded once ------
+ * gh = sc*g; [L2: gh += wd*p]; m = b1*m + (1-b1)*gh; v = b2*v + (1-b2)*gh^2;
+ * p = p*(1 - lr*wd) - (lr / (1-b1^t)) * m / (sqrt(v)/sqrt(1-b2^t) + eps)
+ * sc = grad_scale * coef is passed in as a double. */
+void orc_adam64(int64_t n, const float *g, float *p, float *m, float *v, double sc, float lr,
+                float beta1, float beta2, float eps, float wd, int step, int adamw) {
+    const double b1 = beta1, b2 = beta2, lrd = lr, epsd = eps, wdd = wd;
+    const double bc1 = 1.0 - pow(b1, (double)step), bc2 = 1.0 - pow(b2, (double)step);
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < n; e++) {
+        double gh = sc * (double)g[e], pe = p[e];
+        if (!adamw) gh += wdd * pe;
+        double me = b1 * (double)m[e] + (1.0 - b1) * gh;
+        double ve = b2 * (double)v[e] + (1.0 - b2) * gh * gh;
+        double upd = (lrd / bc1) * me / (sqrt(ve) / sqrt(bc2) + epsd);
+        pe = adamw ? pe * (1.0 - lrd * wdd) - upd : pe - upd;
+        m[e] = (float)me;
+        v[e] = (float)ve;
+        p[e] = (float)pe;
+    }
+}
+
+/* ---- Adam, fp32 literal: every operation rounded to fp32, in this order ------
+ * Scalars that do not depend on the element are formed in fp64 from the fp32
+ * hyper-parameters and rounded to fp32 once. */
+void orc_adam32(int64_t n, const float *g, float *p, float *m, float *v, double sc_d, float lr,
+                float beta1, float beta2, float eps, float wd, int step, int adamw) {
+    const float sc = (float)sc_d;
+    const float omb1 = (float)(1.0 - (double)beta1), omb2 = (float)(1.0 - (double)beta2);
+    const float bc1 = (float)(1.0 - pow((double)beta1, (double)step));
+    const float bc2 = (float)(1.0 - pow((double)beta2, (double)step));
+    const float step_size = (float)((double)lr / (double)bc1);
+    const float sqrt_bc2 = (float)sqrt((double)bc2);
+    const float decay = (float)(1.0 - (double)lr * (double)wd);
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < n; e++) {
+        float gh = sc * g[e], pe = p[e];
+        if (!adamw) gh = gh + wd * pe;
+        float t1 = beta1 * m[e], t2 = omb1 * gh;
+        float me = t1 + t2;
+        float t3 = beta2 * v[e], t4 = gh * gh;
+        float t5 = omb2 * t4;
+        float ve = t3 + t5;
+        float den = sqrtf(ve) / sqrt_bc2;
+        den = den + eps;
+        float q = me / den;
+        float upd = step_size * q;
+        if (adamw) {
+            float pd = pe * decay;
+            pe = pd - upd;
+        } else {
+            pe = pe - upd;
+        }
+        m[e] = me;
+        v[e] = ve;
+        p[e] = pe;
+    }
+}
+
+/* ---- pack: fp32 -> bf16, round to nearest, ties to even ---------------------
+ * NaN stays NaN (quiet bit set, sign kept); infinities are kept. */
+void orc_bf16_rne(const float *p, int64_t n, uint16_t *out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < n; e++) {
+        uint32_t u;
+        memcpy(&u, &p[e], 4);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) {
+            out[e] = (uint16_t)((u >> 16) | 0x0040u);
+        } else {
+            uint32_t keep_lsb = (u >> 16) & 1u;
+            out[e] = (uint16_t)((u + 0x7FFFu + keep_lsb) >> 16);
+        }
+    }
+}
+
+int orc_max_threads(void) {
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+    extern void omp_set_num_threads(int);
+    omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

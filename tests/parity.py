@@ -1,0 +1,49 @@
+"""Tolerances of the parity contract, written once for the CPU and GPU tests.
+
+Integer work, the fold and the pack of a given fp32 value are bit-exact.  The
+fp32 master parameter and the two moments must agree with the fp64 reference
+within 1e-6 relative.  Where a result is the difference of two terms that may
+cancel (the first moment changing sign, a parameter of the size of the step),
+"relative" is taken against the magnitude of the terms, not of the difference.
+"""
+import numpy as np
+
+REL = 1e-6
+
+
+def check_moments_and_params(got_p, got_m, got_v, ref_p, ref_m, ref_v, *, p_old, m_old, g_hat,
+                             beta1=0.9, what=""):
+    """All arrays fp32 (got_*: path under test; ref_*: fp64 evaluation rounded once);
+    g_hat = scaled, clipped gradient as fp64."""
+    b1 = float(np.float32(beta1))
+    ref_p64, ref_m64, ref_v64 = (a.astype(np.float64) for a in (ref_p, ref_m, ref_v))
+    floor_m = np.abs(b1 * m_old.astype(np.float64)) + np.abs((1 - b1) * g_hat)
+    tol_m = REL * np.maximum(np.abs(ref_m64), floor_m)
+    tol_v = REL * np.abs(ref_v64)
+    floor_p = np.abs(p_old.astype(np.float64)) + np.abs(ref_p64 - p_old.astype(np.float64))
+    tol_p = REL * np.maximum(np.abs(ref_p64), floor_p)
+    for name, got, ref, tol in (("m", got_m, ref_m64, tol_m), ("v", got_v, ref_v64, tol_v),
+                                ("p", got_p, ref_p64, tol_p)):
+        bad = np.abs(got.astype(np.float64) - ref) > tol
+        if bad.any():
+            k = int(np.argmax(bad))
+            raise AssertionError(f"{what} {name}[{k}]: got {got[k]!r} want {ref[k]!r} tol {tol[k]:.3e} "
+                                 f"({int(bad.sum())} of {bad.size} outside 1e-6)")
+
+
+def ulp_distance_f32(a, b):
+    """Largest distance in units in the last place between two fp32 arrays."""
+    ia = a.view(np.int32).astype(np.int64)
+    ib = b.view(np.int32).astype(np.int64)
+    ia = np.where(ia < 0, -(ia & 0x7FFFFFFF), ia)
+    ib = np.where(ib < 0, -(ib & 0x7FFFFFFF), ib)
+    return int(np.max(np.abs(ia - ib))) if a.size else 0
+
+
+def check_bf16_within_one_ulp(got_bits, ref_bits, what=""):
+    """bf16 bit patterns (uint16) at most one unit in the last place apart."""
+    def key(h):
+        i = h.astype(np.int32)
+        return np.where(i & 0x8000, -(i & 0x7FFF), i)
+    d = np.abs(key(got_bits) - key(ref_bits))
+    assert d.max(initial=0) <= 1, f"{what} packed bf16 differs by {int(d.max())} ulp"
