@@ -1,0 +1,211 @@
+/*
+ * libparo - the one-GPU share of a PaRO training step's Update stage, for
+ * AMD MI355X (gfx950).
+ *
+ * Paper: "Rethinking Memory and Communication Costs for Efficient Large
+ * Language Model Training" (PaRO + HO-Ring).  Sec. 3.2 describes the Update
+ * stage of PaRO-IGG / IIG / NIG: once the last micro-batch's gradients have
+ * been reduce-scattered, each GPU uses its gradient shard to update the
+ * optimizer state it keeps and produces low-precision parameters, which an
+ * all-gather then distributes.  This library does that per-GPU work:
+ *
+ *   paro_plan           who owns what (Sec. 3.1.1 sharding states, Table 1
+ *                       strategies), in which order the reduce-scatter adds the
+ *                       ranks' contributions (Sec. 3.4 Ring / H-Ring / HO-Ring),
+ *                       and where the packed parameters go;
+ *   paro_reduce_shard   sums the P contributions to this rank's range in that
+ *                       order (fp32), and the sum of squares of the result;
+ *   paro_adam_shard     mixed-precision Adam on the range (Sec. 3.1.2: fp32
+ *                       master copy + two moments = 12 bytes/param), with
+ *                       optional global-norm clipping;
+ *   paro_pack_params    rounds the master parameters to bf16 into the
+ *                       all-gather buffer;
+ *   paro_step_fused     the three in two sweeps over memory (one when not
+ *                       clipping).
+ *
+ * Peer ranks are simulated: their contributions are buffers in this GPU's
+ * memory.  No collective is issued.
+ *
+ * NAMING.  P = number of ranks in the cluster (the paper's N), G = ranks per
+ * group (the paper's M), g = P / G groups.  Rank r is local index i = r % G of
+ * group j = r / G.  A strategy is three letters, parameter / gradient /
+ * optimizer state, each 'N' (not sharded), 'I' (sharded inside the group,
+ * replicated across groups) or 'G' (sharded over all ranks) - Table 1.
+ *
+ * LAYOUT.  The tensors are laid end to end into a flat buffer of
+ * Psi = sum(sizes) elements, cut into P chunks of
+ * L = align * ceil(ceil(Psi / P) / align) elements; elements at and past Psi
+ * are padding (their gradient is 0; their state stays 0).  Block b (0 <= b < G)
+ * is chunks [b*g, (b+1)*g): the intra-group shard of local index b.  Chunk
+ * i*g + j belongs to rank (group j, local i).  A rank's range for a state is its
+ * chunk ('G'), its block ('I') or everything ('N').  Its UPDATE RANGE is the
+ * range of its optimizer state; grad_out, p, m and v below are arrays over the
+ * update range ("shard coordinates": element 0 = first element of the range).
+ *
+ * CONVENTIONS.  Every function returns PARO_OK (0) or a negative error code and
+ * never throws or aborts; paro_last_error() gives the text of the calling
+ * thread's last failure.  The caller owns every buffer it passes in.  The
+ * library owns the plan: its host tables, and - created on the first device
+ * call, on the device that is current then - a few hundred KB of device memory
+ * (tensor offset tables and a scratch array of per-block partial sums).  Device
+ * functions only enqueue work on `stream` (a hipStream_t passed as void*; NULL =
+ * the default stream) and never synchronise; a launch error is reported by the
+ * call that launched.  Calls that run concurrently on ONE plan (different
+ * streams) race on the plan's scratch array; use one plan per stream.  Host
+ * queries are thread-safe; a plan is immutable after creation.  "device" /
+ * "host" below says where a pointer must point.
+ */
+#ifndef PARO_H
+#define PARO_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct paro_plan_s paro_plan_t; /* opaque */
+
+enum { PARO_OK = 0, PARO_EINVAL = -1, PARO_ESTRATEGY = -2, PARO_ERANGE = -3, PARO_ENOMEM = -4,
+       PARO_EHIP = -5, PARO_EALIGN = -6 };
+enum { PARO_SCHED_DEFAULT = -1, PARO_RING = 0, PARO_HRING = 1, PARO_HORING = 2 };
+enum { PARO_BF16 = 0, PARO_F32 = 1 };          /* dtype of a tensor's gradient contributions */
+enum { PARO_CHUNK = 0, PARO_TENSORS = 1 };     /* how the contributions are laid out */
+enum { PARO_RS = 0, PARO_AG = 1 };             /* reduce-scatter, all-gather */
+enum { PARO_MAX_RANKS = 256 };                 /* largest P */
+
+typedef struct {
+    int32_t sched;              /* PARO_SCHED_DEFAULT: HO-Ring when 1 < G < P, else ring */
+    int32_t align_elems;        /* 0 = default 8; otherwise a positive multiple of 8 */
+    const uint8_t *grad_dtype;  /* host [n_tensors] of PARO_BF16/PARO_F32, or NULL = all bf16 */
+    const uint8_t *no_decay;    /* host [n_tensors], nonzero = exempt from weight decay, or NULL */
+} paro_plan_opts_t;
+
+/* a piece of a tensor inside a range */
+typedef struct { int64_t tensor, tensor_off, shard_off, len; } paro_seg_t;
+
+/* one contiguous range of one message of a collective; offsets in elements of
+ * the padded flat buffer.  Entries with equal (phase, ring, step) make up one
+ * logical message; the n-th such entry of the sender pairs with the n-th of
+ * the receiver. */
+typedef struct {
+    int32_t phase, step, ring /* 0 intra-group (or the flat ring), 1 inter-group */, send_to, recv_from;
+    int32_t pad_;
+    int64_t send_off, send_len, recv_off, recv_len;
+} paro_msg_t;
+
+/* Adam hyper-parameters (Kingma & Ba, Algorithm 1; the paper only names the
+ * optimizer).  step is 1 on the first update.  grad_scale multiplies the summed
+ * gradient (1/P gives the mean).  max_norm > 0 clips by global L2 norm:
+ *   coef = min(1, max_norm / (grad_scale * sqrt(total_sumsq) + 1e-6)).
+ * adamw != 0: decoupled decay  p <- p*(1 - lr*wd) - step;  adamw == 0: classic
+ * L2 (wd*p is added to the gradient before the moments). */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay, grad_scale, max_norm;
+    int32_t step, adamw;
+} paro_adam_t;
+
+/* ---- plan (host only; needs no GPU) -------------------------------------- */
+
+/* 1 if the three letters satisfy Principle 1 (Sec. 3.1.3: the optimizer state
+ * is sharded at least as finely as parameters and as gradients) - the 14 rows
+ * of Table 1 - else 0. */
+int paro_strategy_legal(const char *strategy);
+
+/* Builds a plan.  tensor_sizes: host [n_tensors], each >= 0, sum >= 1.
+ * Errors: P < 1, P > PARO_MAX_RANKS, G < 1, P % G != 0, n_tensors < 1, a negative
+ * size, a bad option -> PARO_EINVAL; strategy not in Table 1 -> PARO_ESTRATEGY.
+ * On success *out owns the plan; free it with paro_plan_destroy. */
+int paro_plan(int P, int G, const char *strategy, const int64_t *tensor_sizes, int64_t n_tensors,
+              const paro_plan_opts_t *opts /* nullable */, paro_plan_t **out);
+void paro_plan_destroy(paro_plan_t *plan);
+
+int64_t paro_total(const paro_plan_t *plan);        /* Psi */
+int64_t paro_shard_len(const paro_plan_t *plan);    /* L */
+int64_t paro_padded_total(const paro_plan_t *plan); /* P * L */
+int paro_sched(const paro_plan_t *plan);            /* the resolved schedule kind */
+
+/* chunk owned by a rank under global sharding, and its inverse; < 0 on error */
+int paro_chunk_of_rank(const paro_plan_t *plan, int rank);
+int paro_owner_of_chunk(const paro_plan_t *plan, int chunk);
+
+/* range a rank holds of state 'P' (parameters), 'G' (gradients) or 'O'
+ * (optimizer state = the update range), in elements of the padded flat buffer */
+int paro_range(const paro_plan_t *plan, int rank, char state, int64_t *begin, int64_t *len);
+
+/* pieces of tensors inside the rank's update range, in order; writes at most
+ * cap entries to out (host, may be NULL when cap == 0) and returns the full
+ * count, or a negative error */
+int64_t paro_segments(const paro_plan_t *plan, int rank, paro_seg_t *out, int64_t cap);
+
+/* order in which the reduce-scatter adds the P ranks' contributions to a chunk
+ * (Sec. 3.4): ranks[0..P) (host) lists them; consecutive runs of *group_len
+ * are summed left to right into partials, the partials left to right.  The flat
+ * ring gives *group_len == P; the chunk's owner always comes last. */
+int paro_fold_order(const paro_plan_t *plan, int chunk, int32_t *ranks, int32_t *group_len);
+
+/* message table of a rank for a reduce-scatter (PARO_RS) or all-gather
+ * (PARO_AG) under schedule kind `sched` (PARO_SCHED_DEFAULT = the plan's own).
+ * Same cap / count convention as paro_segments.  Ring: Sec. 3.4 "traditional
+ * Ring"; H-Ring: two sequential steps (intra-group first for a reduce-scatter,
+ * last for an all-gather); HO-Ring: phase 1 = both rings at once on the rank's
+ * own chunk, phase 2 = intra-group ring passing on what the inter-group ring
+ * delivered (all-gather), and the reverse in time for a reduce-scatter. */
+int64_t paro_schedule(const paro_plan_t *plan, int rank, int sched, int collective, paro_msg_t *out,
+                      int64_t cap);
+
+/* where paro_pack_params writes: the rank's low-precision parameter buffer has
+ * *dst_len elements (its 'P' range) and the update range sits at *slot_off in
+ * it, *slot_len long */
+int paro_pack_slot(const paro_plan_t *plan, int rank, int64_t *dst_len, int64_t *slot_off,
+                   int64_t *slot_len);
+
+/* ---- device work ------------------------------------------------------------
+ * contrib: HOST array of P pointers, indexed by rank (contrib[rank] is this
+ * rank's own gradient).
+ *   PARO_CHUNK:   contrib[q] -> DEVICE array over the update range, 16-byte
+ *                 aligned, all of one dtype (every tensor of the plan must have
+ *                 the same grad_dtype).
+ *   PARO_TENSORS: contrib[q] -> DEVICE array of n_tensors DEVICE pointers, the
+ *                 q-th rank's full gradient of each tensor (dtype per tensor as
+ *                 planned; each naturally aligned; empty tensors may be NULL).
+ * grad_out, p, m, v: DEVICE fp32 arrays over the update range, 16-byte aligned.
+ * PARO_EALIGN for a misaligned pointer, PARO_EINVAL for a NULL one. */
+
+/* grad_out[e] = the P contributions to element e added in the fold order of
+ * e's chunk; *sumsq_out (DEVICE double, overwritten) = sum of grad_out[e]^2
+ * over the rank's OWN chunk only, so that adding the ranks' values counts every
+ * element of the model once. */
+int paro_reduce_shard(paro_plan_t *plan, int rank, const void *const *contrib, int layout,
+                      float *grad_out, double *sumsq_out, void *stream);
+
+/* Adam over the update range, in place on p, m, v.  total_sumsq: DEVICE double
+ * = the sum over all ranks of their sumsq_out (read when hp->max_norm > 0; may
+ * be NULL otherwise). */
+int paro_adam_shard(paro_plan_t *plan, int rank, const paro_adam_t *hp, const float *grad,
+                    const double *total_sumsq, float *p, float *m, float *v, void *stream);
+
+/* dst_base[slot_off + e] = bf16(p[e]), round to nearest even, over the update
+ * range.  dst_base: DEVICE uint16 array of dst_len elements (paro_pack_slot),
+ * 16-byte aligned. */
+int paro_pack_params(paro_plan_t *plan, int rank, const float *p, uint16_t *dst_base, void *stream);
+
+/* reduce + clip + Adam + pack.  With hp->max_norm > 0: sweep 1 writes the
+ * reduced gradient to grad_scratch (DEVICE fp32 over the update range) and the
+ * sum of squares to *sumsq_scratch (DEVICE double); sweep 2 clips with THIS
+ * rank's sum of squares as the total (a single-rank norm: the cross-rank sum a
+ * deployment inserts between the sweeps has no peer here), updates and packs.
+ * With hp->max_norm <= 0 one sweep does everything, the gradient is never
+ * stored, and both scratch pointers may be NULL. */
+int paro_step_fused(paro_plan_t *plan, int rank, const void *const *contrib, int layout,
+                    const paro_adam_t *hp, float *grad_scratch, double *sumsq_scratch, float *p,
+                    float *m, float *v, uint16_t *dst_base, void *stream);
+
+/* text of the calling thread's last error ("" if none); valid until that
+ * thread's next failing call */
+const char *paro_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARO_H */

@@ -1,0 +1,835 @@
+// Device side of libparo for gfx950 (MI355X): the streaming kernels of the
+// Update stage (paper Sec. 3.2) and the entry points that launch them.
+//
+// Everything here is bound by HBM bandwidth: per shard parameter the method
+// moves 2P bytes of bf16 contributions and 26-34 bytes of fp32 state, against
+// P adds and ~20 flops.  So the kernels are plain grid-stride sweeps built
+// around 16-byte coalesced accesses, with many independent loads in flight per
+// thread; there is no dense contraction and hence no MFMA.
+//
+//   tile      2048 consecutive elements (256 threads x 8 elements)
+//   grid      persistent: 8 blocks per CU, block b takes tiles b, b+grid, ...
+//             so that blocks running at the same time read neighbouring
+//             addresses of every stream
+//   fold      the P contributions of an element are added in a fixed order
+//             (never re-associated, never contracted into FMAs) so the result
+//             is bit-identical to a reduce-scatter ring run in that order
+//   norm      squares are exact in fp64; per-thread fp64 sums -> wave shuffles
+//             -> LDS -> one partial per block -> a one-block kernel adds the
+//             partials in index order.  No atomics: run-to-run identical.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <string>
+#include <type_traits>
+
+#include "plan.hpp"
+
+namespace {
+
+constexpr int TPB = 256;            // threads per block
+constexpr int EPT = 8;              // elements per thread per tile
+constexpr int TILE = TPB * EPT;     // 2048
+constexpr int BLOCKS_PER_CU = 8;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// P device pointers in fold order.  Lives in the kernel-argument segment and is
+// only ever indexed with wave-uniform indices, i.e. read with scalar loads.
+struct SrcTable {
+    const void *p[PARO_MAX_RANKS];
+};
+
+struct AdamConsts {
+    float beta1, beta2, omb1, omb2, eps, step_size, sqrt_bc2, decay, wd, grad_scale, max_norm;
+    int adamw;
+};
+
+// What the kernels need to map an element of the flat buffer to its tensor.
+struct TensorMap {
+    const int64_t *nz_off;      // [n_nz + 1]
+    const int32_t *nz_tensor;   // [n_nz]
+    const uint8_t *dtype;       // [T]
+    const uint8_t *no_decay;    // [T]
+    int n_nz;
+    int64_t total;              // Psi
+};
+
+// ---------------------------------------------------------------- small helpers
+__device__ __forceinline__ float bf16_lo(unsigned int w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned int w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+__device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;      // NaN stays NaN
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ void load8_f32(const float *p, float x[8]) {
+    f32x4 a = *reinterpret_cast<const f32x4 *>(p);
+    f32x4 b = *reinterpret_cast<const f32x4 *>(p + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+__device__ __forceinline__ void store8_f32(float *p, const float x[8]) {
+    f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
+    *reinterpret_cast<f32x4 *>(p) = a;
+    *reinterpret_cast<f32x4 *>(p + 4) = b;
+}
+
+__device__ __forceinline__ void store8_bf16(uint16_t *p, const float x[8]) {
+    u32x4 w;
+    w.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
+    w.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
+    w.z = f32_to_bf16_rne(x[4]) | (f32_to_bf16_rne(x[5]) << 16);
+    w.w = f32_to_bf16_rne(x[6]) | (f32_to_bf16_rne(x[7]) << 16);
+    *reinterpret_cast<u32x4 *>(p) = w;
+}
+
+// Sum over the block, valid in thread 0.  Fixed shape: lanes by shuffles, then
+// the four waves in order.
+__device__ __forceinline__ double block_sum(double v) {
+    __shared__ double s_wave[TPB / 64];
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) s_wave[wave] = v;
+    __syncthreads();
+    double r = 0.0;
+    if (threadIdx.x == 0) {
+        r = s_wave[0];
+        for (int w = 1; w < TPB / 64; ++w) r += s_wave[w];
+    }
+    __syncthreads();
+    return r;
+}
+
+// Where the thread's 8 elements live: tensor (-1 = padding) and offset inside it.
+struct Where8 {
+    int tens[8];
+    int64_t toff[8];
+    bool one_tensor;       // all 8 in one tensor (then tens[0], toff[0] describe them)
+};
+
+// ------------------------------------------------------------------- loaders
+// A loader hands the fold the 8 values that contribution k (in fold order)
+// holds for the thread's 8 elements.
+
+// Contributions are arrays in shard coordinates, all bf16 or all fp32.
+template <int DT>
+struct ChunkLoader {
+    static constexpr bool kTensor = false;
+    // contributions loaded before the first is consumed (16 bytes each for bf16, 32 for fp32)
+    static constexpr int kBatch = DT == PARO_BF16 ? 16 : 8;
+    struct Raw { u32x4 a, b; };
+    int64_t e;                                   // first of the thread's 8 elements
+    __device__ __forceinline__ void prepare(int64_t e0, const Where8 &) { e = e0; }
+    __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
+        if (DT == PARO_BF16) {
+            r.a = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(src.p[k]) + e);
+        } else {
+            const u32x4 *q = reinterpret_cast<const u32x4 *>(static_cast<const float *>(src.p[k]) + e);
+            r.a = q[0];
+            r.b = q[1];
+        }
+    }
+    __device__ __forceinline__ void unpack(const Raw &r, float x[8]) const {
+        if (DT == PARO_BF16) {
+            x[0] = bf16_lo(r.a.x); x[1] = bf16_hi(r.a.x); x[2] = bf16_lo(r.a.y); x[3] = bf16_hi(r.a.y);
+            x[4] = bf16_lo(r.a.z); x[5] = bf16_hi(r.a.z); x[6] = bf16_lo(r.a.w); x[7] = bf16_hi(r.a.w);
+        } else {
+            x[0] = __uint_as_float(r.a.x); x[1] = __uint_as_float(r.a.y);
+            x[2] = __uint_as_float(r.a.z); x[3] = __uint_as_float(r.a.w);
+            x[4] = __uint_as_float(r.b.x); x[5] = __uint_as_float(r.b.y);
+            x[6] = __uint_as_float(r.b.z); x[7] = __uint_as_float(r.b.w);
+        }
+    }
+};
+
+// Largest k in [0, n_entries) with tab[k] <= f, for a sorted table with
+// tab[0] <= f; the 64 lanes of a wave probe 64 places per round.
+__device__ __forceinline__ int wave_search(const int64_t *tab, int n_entries, int64_t f, int lane) {
+    int lo = 0, hi = n_entries;
+    while (hi - lo > 1) {
+        const int step = (hi - lo + 63) / 64;
+        const int idx = lo + lane * step;
+        const bool le = idx < hi && tab[idx] <= f;
+        const int cnt = __popcll(__ballot(le));        // the lanes that hold form a prefix
+        lo = lo + (cnt - 1) * step;
+        hi = min(hi, lo + step);
+    }
+    return lo;
+}
+
+// The slice of the tensor-offset table that covers one tile, staged in LDS, so
+// that the ragged side of the work (which tensor, which offset) costs LDS
+// lookups instead of dependent global loads.
+struct TileSegs {
+    int64_t *s_off;        // [TILE + 2], tile-relative starts of the segments, then the end of the last
+    int *s_head;           // [2]: index of the first segment in the table, segment count
+    TensorMap tm;
+    int64_t range_begin;   // flat index of shard element 0
+
+    __device__ __forceinline__ void begin_tile(int64_t tile_start) {
+        const int64_t f0 = range_begin + tile_start;
+        const int64_t f_end = min(f0 + (int64_t)TILE, tm.total);
+        __syncthreads();                                   // the previous tile's readers are done
+        if (threadIdx.x < 64) {
+            int k_lo = tm.n_nz;
+            if (f0 < tm.total) k_lo = wave_search(tm.nz_off, tm.n_nz + 1, f0, threadIdx.x);
+            if (threadIdx.x == 0) {
+                s_head[0] = k_lo;
+                s_head[1] = 0;
+            }
+        }
+        __syncthreads();
+        const int k_lo = s_head[0];
+        // segments are at least one element long, so a tile sees at most TILE of them
+        for (int base = 0; base <= TILE; base += TPB) {
+            const int c = base + threadIdx.x;
+            int64_t val = INT64_MAX;
+            if (c <= TILE && k_lo + c <= tm.n_nz) {
+                val = tm.nz_off[k_lo + c];
+                s_off[c] = val - f0;
+                if (val < f_end) atomicMax(&s_head[1], c + 1);
+            }
+            // stop once a whole round lies at or past the end of the tile
+            const int more = __syncthreads_or(val < f_end);
+            if (!more) break;
+        }
+    }
+    __device__ __forceinline__ int count() const { return s_head[1]; }
+    __device__ __forceinline__ int first() const { return s_head[0]; }
+    // segment (tile-local index) holding tile-relative element rel, or -1 for padding
+    __device__ __forceinline__ int find(int rel) const {
+        const int n = s_head[1];
+        if (n == 0 || (int64_t)rel >= s_off[n]) return -1;
+        int lo = 0, hi = n;                                 // s_off[lo] <= rel < s_off[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (s_off[mid] <= rel) lo = mid; else hi = mid;
+        }
+        return lo;
+    }
+};
+
+__device__ __forceinline__ void locate8(const TileSegs &segs, int rel0, Where8 &w) {
+    int c = segs.find(rel0);
+    const int n = segs.count();
+    const int c_first = c;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int rel = rel0 + i;
+        if (c >= 0) {
+            while (c < n && segs.s_off[c + 1] <= rel) ++c;
+            if (c >= n) c = -1;                            // ran into the padding
+        }
+        if (c >= 0) {
+            w.tens[i] = segs.tm.nz_tensor[segs.first() + c];
+            w.toff[i] = (int64_t)rel - segs.s_off[c];
+        } else {
+            w.tens[i] = -1;
+            w.toff[i] = 0;
+        }
+    }
+    w.one_tensor = c_first >= 0 && c == c_first;
+}
+
+// Contributions are per-tensor gradients: source k is a device array of T
+// pointers.  Elements map to tensors through the staged offsets.
+struct TensorLoader {
+    static constexpr bool kTensor = true;
+    static constexpr int kBatch = 4;
+    struct Raw { float x[8]; };
+    const uint8_t *dtype;  // [T]
+    const Where8 *w;
+
+    __device__ __forceinline__ void prepare(int64_t, const Where8 &where) { w = &where; }
+    __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
+        const void *const *ptrs = static_cast<const void *const *>(src.p[k]);
+        if (w->one_tensor) {
+            const int t = w->tens[0];
+            const bool is_bf16 = dtype[t] == PARO_BF16;
+            const char *base = static_cast<const char *>(ptrs[t]) + w->toff[0] * (is_bf16 ? 2 : 4);
+            if ((reinterpret_cast<uintptr_t>(base) & 15) == 0) {
+                if (is_bf16) {
+                    u32x4 q = *reinterpret_cast<const u32x4 *>(base);
+                    r.x[0] = bf16_lo(q.x); r.x[1] = bf16_hi(q.x); r.x[2] = bf16_lo(q.y); r.x[3] = bf16_hi(q.y);
+                    r.x[4] = bf16_lo(q.z); r.x[5] = bf16_hi(q.z); r.x[6] = bf16_lo(q.w); r.x[7] = bf16_hi(q.w);
+                } else {
+                    load8_f32(reinterpret_cast<const float *>(base), r.x);
+                }
+            } else if (is_bf16) {
+                const uint16_t *h = reinterpret_cast<const uint16_t *>(base);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r.x[i] = __uint_as_float((unsigned int)h[i] << 16);
+            } else {
+                const float *f = reinterpret_cast<const float *>(base);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r.x[i] = f[i];
+            }
+            return;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float val = 0.0f;                               // padding contributes +0
+            const int t = w->tens[i];
+            if (t >= 0) {
+                const void *b = ptrs[t];
+                if (dtype[t] == PARO_BF16)
+                    val = __uint_as_float((unsigned int)static_cast<const uint16_t *>(b)[w->toff[i]] << 16);
+                else
+                    val = static_cast<const float *>(b)[w->toff[i]];
+            }
+            r.x[i] = val;
+        }
+    }
+    __device__ __forceinline__ void unpack(const Raw &r, float x[8]) const {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = r.x[i];
+    }
+};
+
+// ---------------------------------------------------------------------- fold
+// X[i] = contributions added in table order: runs of group_len into a partial A
+// (left to right), partials into X (left to right).  The first value of a run
+// and the first partial are copied, not added to zero (that would lose -0).
+template <class Ld>
+__device__ __forceinline__ void fold8(const Ld &ld, const SrcTable &src, int P, int group_len, float X[8]) {
+    float A[8];
+    int pos = 0;
+    bool first_group = true;
+    constexpr int FOLD_BATCH = Ld::kBatch;
+    for (int k0 = 0; k0 < P; k0 += FOLD_BATCH) {
+        typename Ld::Raw raw[FOLD_BATCH];
+#pragma unroll
+        for (int b = 0; b < FOLD_BATCH; ++b)
+            if (k0 + b < P) ld.load(src, k0 + b, raw[b]);
+#pragma unroll
+        for (int b = 0; b < FOLD_BATCH; ++b) {
+            if (k0 + b < P) {
+                float x[8];
+                ld.unpack(raw[b], x);
+                if (pos == 0) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) A[i] = x[i];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) A[i] = A[i] + x[i];
+                }
+                if (++pos == group_len) {
+                    pos = 0;
+                    if (first_group) {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) X[i] = A[i];
+                        first_group = false;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) X[i] = X[i] + A[i];
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------- Adam
+// sc = grad_scale * clip coefficient, from the global sum of squares.
+__device__ __forceinline__ float scale_from_norm(const AdamConsts &a, const double *total_sumsq) {
+    double coef = 1.0;
+    if (a.max_norm > 0.0f) {
+        const double norm = (double)a.grad_scale * sqrt(*total_sumsq);
+        const double c = (double)a.max_norm / (norm + 1e-6);
+        coef = c < 1.0 ? c : 1.0;
+    }
+    return (float)((double)a.grad_scale * coef);
+}
+
+// One element.  Every operation is a separate fp32 rounding, in this order
+// (the library is compiled without FMA contraction).
+__device__ __forceinline__ void adam1(const AdamConsts &a, float sc, bool decays, float g, float &p, float &m,
+                                      float &v) {
+    float gh = sc * g;
+    if (!a.adamw && decays) gh = gh + a.wd * p;
+    const float t1 = a.beta1 * m, t2 = a.omb1 * gh;
+    m = t1 + t2;
+    const float t3 = a.beta2 * v, t4 = gh * gh;
+    const float t5 = a.omb2 * t4;
+    v = t3 + t5;
+    float den = sqrtf(v) / a.sqrt_bc2;
+    den = den + a.eps;
+    const float q = m / den;
+    const float upd = a.step_size * q;
+    if (a.adamw && decays) {
+        const float pd = p * a.decay;
+        p = pd - upd;
+    } else {
+        p = p - upd;
+    }
+}
+
+// --------------------------------------------------------------------- kernels
+// Sweep 1: g = fold of the contributions; optional per-block partial of sum g^2.
+template <class Ld, bool SUMSQ>
+__global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P, int group_len, int64_t n,
+                                                float *__restrict__ g, double *__restrict__ partials,
+                                                TileSegs segs) {
+    __shared__ int64_t s_off[Ld::kTensor ? TILE + 2 : 1];
+    __shared__ int s_head[2];
+    segs.s_off = s_off;
+    segs.s_head = s_head;
+    double acc = 0.0;
+    const int64_t ntiles = (n + TILE - 1) / TILE;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (Ld::kTensor) segs.begin_tile(tile * TILE);
+        const int rel0 = threadIdx.x * EPT;
+        const int64_t e = tile * TILE + rel0;
+        if (e < n) {
+            Where8 w;
+            if (Ld::kTensor) locate8(segs, rel0, w);
+            ld.prepare(e, w);
+            float X[8];
+            fold8(ld, src, P, group_len, X);
+            store8_f32(g + e, X);
+            if (SUMSQ) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc += (double)X[i] * (double)X[i];
+            }
+        }
+    }
+    if (SUMSQ) {
+        const double s = block_sum(acc);
+        if (threadIdx.x == 0) partials[blockIdx.x] = s;
+    }
+}
+
+// Adds the per-block partials in index order (thread t takes t, t+256, ...; then
+// the fixed block tree).
+__global__ __launch_bounds__(TPB) void k_finalize(const double *__restrict__ partials, int n, double *out) {
+    double acc = 0.0;
+    for (int k = threadIdx.x; k < n; k += TPB) acc += partials[k];
+    const double s = block_sum(acc);
+    if (threadIdx.x == 0) *out = s;
+}
+
+// Sweep 2: Adam on the stored gradient, optionally packing bf16 parameters and
+// optionally with a per-tensor weight-decay mask.
+template <bool PACK, bool MASK>
+__global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *__restrict__ total_sumsq,
+                                              const float *__restrict__ g, float *__restrict__ p,
+                                              float *__restrict__ m, float *__restrict__ v,
+                                              uint16_t *__restrict__ dst, int64_t n, TileSegs segs) {
+    __shared__ int64_t s_off[MASK ? TILE + 2 : 1];
+    __shared__ int s_head[2];
+    segs.s_off = s_off;
+    segs.s_head = s_head;
+    const float sc = scale_from_norm(a, total_sumsq);
+    const int64_t ntiles = (n + TILE - 1) / TILE;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (MASK) segs.begin_tile(tile * TILE);
+        const int rel0 = threadIdx.x * EPT;
+        const int64_t e = tile * TILE + rel0;
+        if (e < n) {
+            bool decays[8];
+            if (MASK) {
+                Where8 w;
+                locate8(segs, rel0, w);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) decays[i] = w.tens[i] < 0 || segs.tm.no_decay[w.tens[i]] == 0;
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) decays[i] = true;
+            }
+            float gg[8], pp[8], mm[8], vv[8];
+            load8_f32(g + e, gg);
+            load8_f32(p + e, pp);
+            load8_f32(m + e, mm);
+            load8_f32(v + e, vv);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) adam1(a, sc, decays[i], gg[i], pp[i], mm[i], vv[i]);
+            store8_f32(p + e, pp);
+            store8_f32(m + e, mm);
+            store8_f32(v + e, vv);
+            if (PACK) store8_bf16(dst + e, pp);
+        }
+    }
+}
+
+// Single sweep when nothing has to wait for the norm: fold, Adam and pack; the
+// reduced gradient never goes to memory.
+template <class Ld, bool MASK>
+__global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P, int group_len, int64_t n,
+                                               const AdamConsts a, float *__restrict__ p, float *__restrict__ m,
+                                               float *__restrict__ v, uint16_t *__restrict__ dst, TileSegs segs) {
+    constexpr bool NEED_SEGS = Ld::kTensor || MASK;
+    __shared__ int64_t s_off[NEED_SEGS ? TILE + 2 : 1];
+    __shared__ int s_head[2];
+    segs.s_off = s_off;
+    segs.s_head = s_head;
+    const float sc = a.grad_scale;                     // no clipping on this path
+    const int64_t ntiles = (n + TILE - 1) / TILE;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        if (NEED_SEGS) segs.begin_tile(tile * TILE);
+        const int rel0 = threadIdx.x * EPT;
+        const int64_t e = tile * TILE + rel0;
+        if (e < n) {
+            Where8 w;
+            if (NEED_SEGS) locate8(segs, rel0, w);
+            ld.prepare(e, w);
+            float pp[8], mm[8], vv[8], X[8];
+            load8_f32(p + e, pp);
+            load8_f32(m + e, mm);
+            load8_f32(v + e, vv);
+            fold8(ld, src, P, group_len, X);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                bool decays = true;
+                if (MASK) decays = w.tens[i] < 0 || segs.tm.no_decay[w.tens[i]] == 0;
+                adam1(a, sc, decays, X[i], pp[i], mm[i], vv[i]);
+            }
+            store8_f32(p + e, pp);
+            store8_f32(m + e, mm);
+            store8_f32(v + e, vv);
+            store8_bf16(dst + e, pp);
+        }
+    }
+}
+
+// bf16 pack alone.
+__global__ __launch_bounds__(TPB) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n) {
+    const int64_t ntiles = (n + TILE - 1) / TILE;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const int64_t e = tile * TILE + threadIdx.x * EPT;
+        if (e < n) {
+            float pp[8];
+            load8_f32(p + e, pp);
+            store8_bf16(dst + e, pp);
+        }
+    }
+}
+
+}  // namespace
+
+// =========================================================================
+// host side: validation and launches
+// =========================================================================
+namespace {
+
+using paro::fail;
+
+#define PARO_HIP(expr)                                                                             \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail(PARO_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+int check_ptr(const void *p, const char *what) {
+    if (!p) return fail(PARO_EINVAL, std::string(what) + " is NULL");
+    if (reinterpret_cast<uintptr_t>(p) & 15) return fail(PARO_EALIGN, std::string(what) + " is not 16-byte aligned");
+    return PARO_OK;
+}
+
+template <class T>
+int upload(T **dst, const T *src, size_t n) {
+    PARO_HIP(hipMalloc(reinterpret_cast<void **>(dst), (n ? n : 1) * sizeof(T)));
+    if (n) PARO_HIP(hipMemcpy(*dst, src, n * sizeof(T), hipMemcpyHostToDevice));
+    return PARO_OK;
+}
+
+// Creates the plan's device tables on the current device, once.
+int ensure_device(paro_plan_t *pl) {
+    std::lock_guard<std::mutex> lock(pl->dev_mutex);
+    int dev = -1;
+    PARO_HIP(hipGetDevice(&dev));
+    if (pl->dev.device >= 0) {
+        if (pl->dev.device != dev)
+            return fail(PARO_EINVAL, "the plan's device tables live on another device than the current one");
+        return PARO_OK;
+    }
+    paro_device_tables d;
+    PARO_HIP(hipDeviceGetAttribute(&d.n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (d.n_cu < 1) d.n_cu = 256;
+    int rc;
+    if ((rc = upload(&d.nz_off, pl->nz_off.data(), pl->nz_off.size()))) return rc;
+    if ((rc = upload(&d.nz_tensor, pl->nz_tensor.data(), pl->nz_tensor.size()))) return rc;
+    if ((rc = upload(&d.dtype, pl->dtype.data(), pl->dtype.size()))) return rc;
+    if ((rc = upload(&d.no_decay, pl->no_decay.data(), pl->no_decay.size()))) return rc;
+    PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), PARO_MAX_PARTIALS * sizeof(double)));
+    d.device = dev;
+    pl->dev = d;
+    return PARO_OK;
+}
+
+int grid_for(const paro_plan_t *pl, int64_t n) {
+    const int64_t ntiles = (n + TILE - 1) / TILE;
+    int64_t cap = (int64_t)pl->dev.n_cu * BLOCKS_PER_CU;
+    if (cap > PARO_MAX_PARTIALS) cap = PARO_MAX_PARTIALS;
+    return (int)(ntiles < cap ? (ntiles < 1 ? 1 : ntiles) : cap);
+}
+
+TileSegs segs_for(const paro_plan_t *pl, int64_t range_begin) {
+    TileSegs s;
+    s.s_off = nullptr;
+    s.s_head = nullptr;
+    s.tm.nz_off = pl->dev.nz_off;
+    s.tm.nz_tensor = pl->dev.nz_tensor;
+    s.tm.dtype = pl->dev.dtype;
+    s.tm.no_decay = pl->dev.no_decay;
+    s.tm.n_nz = (int)pl->nz_tensor.size();
+    s.tm.total = pl->total;
+    s.range_begin = range_begin;
+    return s;
+}
+
+int check_common(const paro_plan_t *pl, int rank, const char *fn) {
+    if (!pl) return fail(PARO_EINVAL, std::string(fn) + ": plan is NULL");
+    if (rank < 0 || rank >= pl->P) return fail(PARO_ERANGE, std::string(fn) + ": rank out of range");
+    return PARO_OK;
+}
+
+int check_contrib(const paro_plan_t *pl, const void *const *contrib, int layout, const char *fn) {
+    if (!contrib) return fail(PARO_EINVAL, std::string(fn) + ": contrib is NULL");
+    if (layout != PARO_CHUNK && layout != PARO_TENSORS) return fail(PARO_EINVAL, std::string(fn) + ": bad layout");
+    if (layout == PARO_CHUNK && !pl->uniform_dtype)
+        return fail(PARO_EINVAL, std::string(fn) + ": chunk layout needs one gradient dtype for all tensors");
+    for (int q = 0; q < pl->P; ++q) {
+        if (!contrib[q]) return fail(PARO_EINVAL, std::string(fn) + ": a contribution pointer is NULL");
+        if (layout == PARO_CHUNK && (reinterpret_cast<uintptr_t>(contrib[q]) & 15))
+            return fail(PARO_EALIGN, std::string(fn) + ": a contribution is not 16-byte aligned");
+        if (layout == PARO_TENSORS && (reinterpret_cast<uintptr_t>(contrib[q]) & 7))
+            return fail(PARO_EALIGN, std::string(fn) + ": a pointer table is not 8-byte aligned");
+    }
+    return PARO_OK;
+}
+
+int adam_consts(const paro_adam_t *hp, AdamConsts *a, const char *fn) {
+    if (!hp) return fail(PARO_EINVAL, std::string(fn) + ": hp is NULL");
+    if (hp->step < 1) return fail(PARO_EINVAL, std::string(fn) + ": step must be >= 1");
+    if (!(hp->beta1 >= 0.0f && hp->beta1 < 1.0f && hp->beta2 >= 0.0f && hp->beta2 < 1.0f))
+        return fail(PARO_EINVAL, std::string(fn) + ": betas must lie in [0, 1)");
+    // element-independent scalars: formed in fp64 from the fp32 hyper-parameters, rounded once
+    const double b1 = hp->beta1, b2 = hp->beta2;
+    const float bc1 = (float)(1.0 - std::pow(b1, (double)hp->step));
+    const float bc2 = (float)(1.0 - std::pow(b2, (double)hp->step));
+    a->beta1 = hp->beta1;
+    a->beta2 = hp->beta2;
+    a->omb1 = (float)(1.0 - b1);
+    a->omb2 = (float)(1.0 - b2);
+    a->eps = hp->eps;
+    a->step_size = (float)((double)hp->lr / (double)bc1);
+    a->sqrt_bc2 = (float)std::sqrt((double)bc2);
+    a->decay = (float)(1.0 - (double)hp->lr * (double)hp->weight_decay);
+    a->wd = hp->weight_decay;
+    a->grad_scale = hp->grad_scale;
+    a->max_norm = hp->max_norm;
+    a->adamw = hp->adamw ? 1 : 0;
+    return PARO_OK;
+}
+
+// Pointer table of a chunk in fold order.  Chunk layout: pointers advanced to the
+// chunk's first element inside the update range.
+void src_table(const paro_plan_t *pl, int chunk, const void *const *contrib, int layout, int64_t chunk_off_in_range,
+               SrcTable *tab, int *group_len) {
+    int32_t order[PARO_MAX_RANKS];
+    int32_t gl = 0;
+    paro::fold_order(pl, chunk, order, &gl);
+    const int64_t esize = pl->dtype[0] == PARO_BF16 ? 2 : 4;
+    for (int k = 0; k < pl->P; ++k) {
+        const char *base = static_cast<const char *>(contrib[order[k]]);
+        tab->p[k] = layout == PARO_CHUNK ? base + chunk_off_in_range * esize : base;
+    }
+    for (int k = pl->P; k < PARO_MAX_RANKS; ++k) tab->p[k] = nullptr;
+    *group_len = gl;
+}
+
+template <bool SUMSQ>
+void launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t flat_begin, float *g,
+                   hipStream_t st) {
+    const int64_t n = pl->L;
+    const int grid = grid_for(pl, n);
+    TileSegs segs = segs_for(pl, flat_begin);
+    double *partials = pl->dev.partials;
+    if (layout == PARO_TENSORS) {
+        TensorLoader ld{pl->dev.dtype, nullptr};
+        hipLaunchKernelGGL((k_reduce<TensorLoader, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, g,
+                           partials, segs);
+    } else if (pl->dtype[0] == PARO_BF16) {
+        ChunkLoader<PARO_BF16> ld{0};
+        hipLaunchKernelGGL((k_reduce<ChunkLoader<PARO_BF16>, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
+                           group_len, n, g, partials, segs);
+    } else {
+        ChunkLoader<PARO_F32> ld{0};
+        hipLaunchKernelGGL((k_reduce<ChunkLoader<PARO_F32>, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
+                           group_len, n, g, partials, segs);
+    }
+}
+
+template <bool MASK>
+void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t flat_begin,
+                  const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
+    const int64_t n = pl->L;
+    const int grid = grid_for(pl, n);
+    TileSegs segs = segs_for(pl, flat_begin);
+    if (layout == PARO_TENSORS) {
+        TensorLoader ld{pl->dev.dtype, nullptr};
+        hipLaunchKernelGGL((k_fused<TensorLoader, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, a,
+                           p, m, v, dst, segs);
+    } else if (pl->dtype[0] == PARO_BF16) {
+        ChunkLoader<PARO_BF16> ld{0};
+        hipLaunchKernelGGL((k_fused<ChunkLoader<PARO_BF16>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
+                           group_len, n, a, p, m, v, dst, segs);
+    } else {
+        ChunkLoader<PARO_F32> ld{0};
+        hipLaunchKernelGGL((k_fused<ChunkLoader<PARO_F32>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
+                           group_len, n, a, p, m, v, dst, segs);
+    }
+}
+
+// Sweep 1 over the whole update range, chunk by chunk; the sum of squares covers
+// the rank's own chunk only.
+int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout, float *grad_out, double *sumsq_out,
+              hipStream_t st) {
+    int64_t ob, on;
+    paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
+    const int own = paro::chunk_of_rank(pl, rank);
+    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {
+        SrcTable tab;
+        int gl;
+        const int64_t lo = c * pl->L - ob;
+        src_table(pl, (int)c, contrib, layout, lo, &tab, &gl);
+        if (c == own && sumsq_out)
+            launch_reduce<true>(pl, layout, tab, gl, c * pl->L, grad_out + lo, st);
+        else
+            launch_reduce<false>(pl, layout, tab, gl, c * pl->L, grad_out + lo, st);
+        PARO_HIP(hipGetLastError());
+    }
+    if (sumsq_out) {
+        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(TPB), 0, st, pl->dev.partials, grid_for(pl, pl->L), sumsq_out);
+        PARO_HIP(hipGetLastError());
+    }
+    return PARO_OK;
+}
+
+int do_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, const double *total_sumsq, float *p,
+            float *m, float *v, uint16_t *dst /* nullable: no pack */, hipStream_t st) {
+    int64_t ob, on;
+    paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
+    const int grid = grid_for(pl, on);
+    TileSegs segs = segs_for(pl, ob);
+    const bool mask = pl->any_no_decay;
+    if (dst && mask)
+        hipLaunchKernelGGL((k_adam<true, true>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
+    else if (dst)
+        hipLaunchKernelGGL((k_adam<true, false>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
+    else if (mask)
+        hipLaunchKernelGGL((k_adam<false, true>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
+    else
+        hipLaunchKernelGGL((k_adam<false, false>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
+    PARO_HIP(hipGetLastError());
+    return PARO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+void paro_plan_destroy(paro_plan_t *pl) {
+    if (!pl) return;
+    if (pl->dev.device >= 0) {
+        // frees are best effort: the plan may outlive the HIP runtime at process exit
+        (void)hipFree(pl->dev.nz_off);
+        (void)hipFree(pl->dev.nz_tensor);
+        (void)hipFree(pl->dev.dtype);
+        (void)hipFree(pl->dev.no_decay);
+        (void)hipFree(pl->dev.partials);
+    }
+    delete pl;
+}
+
+int paro_reduce_shard(paro_plan_t *pl, int rank, const void *const *contrib, int layout, float *grad_out,
+                      double *sumsq_out, void *stream) {
+    int rc;
+    if ((rc = check_common(pl, rank, "paro_reduce_shard"))) return rc;
+    if ((rc = check_contrib(pl, contrib, layout, "paro_reduce_shard"))) return rc;
+    if ((rc = check_ptr(grad_out, "paro_reduce_shard: grad_out"))) return rc;
+    if (sumsq_out && (reinterpret_cast<uintptr_t>(sumsq_out) & 7))
+        return fail(PARO_EALIGN, "paro_reduce_shard: sumsq_out is not 8-byte aligned");
+    if ((rc = ensure_device(pl))) return rc;
+    return do_reduce(pl, rank, contrib, layout, grad_out, sumsq_out, static_cast<hipStream_t>(stream));
+}
+
+int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const float *grad, const double *total_sumsq,
+                    float *p, float *m, float *v, void *stream) {
+    int rc;
+    AdamConsts a;
+    if ((rc = check_common(pl, rank, "paro_adam_shard"))) return rc;
+    if ((rc = adam_consts(hp, &a, "paro_adam_shard"))) return rc;
+    if ((rc = check_ptr(grad, "paro_adam_shard: grad"))) return rc;
+    if ((rc = check_ptr(p, "paro_adam_shard: p"))) return rc;
+    if ((rc = check_ptr(m, "paro_adam_shard: m"))) return rc;
+    if ((rc = check_ptr(v, "paro_adam_shard: v"))) return rc;
+    if (a.max_norm > 0.0f && !total_sumsq)
+        return fail(PARO_EINVAL, "paro_adam_shard: clipping needs total_sumsq");
+    if ((rc = ensure_device(pl))) return rc;
+    return do_adam(pl, rank, a, grad, total_sumsq, p, m, v, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int paro_pack_params(paro_plan_t *pl, int rank, const float *p, uint16_t *dst_base, void *stream) {
+    int rc;
+    if ((rc = check_common(pl, rank, "paro_pack_params"))) return rc;
+    if ((rc = check_ptr(p, "paro_pack_params: p"))) return rc;
+    if ((rc = check_ptr(dst_base, "paro_pack_params: dst_base"))) return rc;
+    if ((rc = ensure_device(pl))) return rc;
+    int64_t dl, so, sl;
+    paro_pack_slot(pl, rank, &dl, &so, &sl);
+    hipLaunchKernelGGL(k_pack, dim3(grid_for(pl, sl)), dim3(TPB), 0, static_cast<hipStream_t>(stream), p,
+                       dst_base + so, sl);
+    PARO_HIP(hipGetLastError());
+    return PARO_OK;
+}
+
+int paro_step_fused(paro_plan_t *pl, int rank, const void *const *contrib, int layout, const paro_adam_t *hp,
+                    float *grad_scratch, double *sumsq_scratch, float *p, float *m, float *v, uint16_t *dst_base,
+                    void *stream) {
+    int rc;
+    AdamConsts a;
+    if ((rc = check_common(pl, rank, "paro_step_fused"))) return rc;
+    if ((rc = check_contrib(pl, contrib, layout, "paro_step_fused"))) return rc;
+    if ((rc = adam_consts(hp, &a, "paro_step_fused"))) return rc;
+    if ((rc = check_ptr(p, "paro_step_fused: p"))) return rc;
+    if ((rc = check_ptr(m, "paro_step_fused: m"))) return rc;
+    if ((rc = check_ptr(v, "paro_step_fused: v"))) return rc;
+    if ((rc = check_ptr(dst_base, "paro_step_fused: dst_base"))) return rc;
+    const bool clip = a.max_norm > 0.0f;
+    if (clip) {
+        if ((rc = check_ptr(grad_scratch, "paro_step_fused: grad_scratch"))) return rc;
+        if (!sumsq_scratch || (reinterpret_cast<uintptr_t>(sumsq_scratch) & 7))
+            return fail(sumsq_scratch ? PARO_EALIGN : PARO_EINVAL, "paro_step_fused: clipping needs sumsq_scratch");
+    }
+    if ((rc = ensure_device(pl))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int64_t dl, so, sl, ob, on;
+    paro_pack_slot(pl, rank, &dl, &so, &sl);
+    uint16_t *dst = dst_base + so;
+    if (clip) {
+        if ((rc = do_reduce(pl, rank, contrib, layout, grad_scratch, sumsq_scratch, st))) return rc;
+        return do_adam(pl, rank, a, grad_scratch, sumsq_scratch, p, m, v, dst, st);
+    }
+    paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
+    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {
+        SrcTable tab;
+        int gl;
+        const int64_t lo = c * pl->L - ob;
+        src_table(pl, (int)c, contrib, layout, lo, &tab, &gl);
+        if (pl->any_no_decay)
+            launch_fused<true>(pl, layout, tab, gl, c * pl->L, a, p + lo, m + lo, v + lo, dst + lo, st);
+        else
+            launch_fused<false>(pl, layout, tab, gl, c * pl->L, a, p + lo, m + lo, v + lo, dst + lo, st);
+        PARO_HIP(hipGetLastError());
+    }
+    return PARO_OK;
+}
+
+}  // extern "C"
