@@ -158,27 +158,36 @@ def chunk_contribs(P: int, n: int, base_seed: int, step: int = 0, *, dist="norma
     return out
 
 
+@dataclass
+class TensorSet:
+    """One simulated rank's full gradients: tensors[t] is a view into flat[dtype]
+    starting at element start[t]."""
+    tensors: List[torch.Tensor]
+    flat: dict
+    start: List[int]
+
+
 def tensor_contribs(P: int, sizes: List[int], dtypes: Optional[List[int]], base_seed: int,
-                    step: int = 0, *, dist="normal", device="cpu") -> List[List[torch.Tensor]]:
+                    step: int = 0, *, dist="normal", device="cpu", align_elems: int = 128) -> List[TensorSet]:
     """Per simulated rank, one full gradient per tensor.  Values are drawn as one
-    flat stream per (rank, dtype) and cut into tensors, so the cost does not
-    depend on the tensor count."""
-    total = sum(sizes)
+    flat stream per (rank, dtype) and tensors are views into it, each starting on
+    a multiple of align_elems elements (128 = the alignment separate allocations
+    would have; 1 = packed tight, arbitrary base alignment)."""
+    kinds = sorted(set(dtypes)) if dtypes is not None else [BF16]
+    start, fill = [], {k: 0 for k in kinds}
+    for t, n in enumerate(sizes):
+        k = dtypes[t] if dtypes is not None else BF16
+        start.append(fill[k])
+        fill[k] += -(-n // align_elems) * align_elems
     out = []
     for q in range(P):
-        flat = {}
-        kinds = set(dtypes) if dtypes is not None else {BF16}
-        for k in sorted(kinds):
-            flat[k] = draw(total, _seed(base_seed, step, q, salt=k + 1), dist=dist, dtype=k,
-                           device=device)
+        flat = {k: draw(max(fill[k], 1), _seed(base_seed, step, q, salt=k + 1), dist=dist, dtype=k, device=device)
+                for k in kinds}
         per = []
-        off = 0
         for t, n in enumerate(sizes):
             k = dtypes[t] if dtypes is not None else BF16
-            # .clone() so every tensor is its own allocation with its own base address
-            per.append(flat[k][off:off + n].clone())
-            off += n
-        out.append(per)
+            per.append(flat[k][start[t]:start[t] + n])
+        out.append(TensorSet(per, flat, start))
     return out
 
 
