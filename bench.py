@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the PaRO update-stage hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input that is
+already resident in HBM: sweep 1 (ordered fold of the P gradient contributions
++ sum of squares) and sweep 2 (clip + Adam + bf16 pack).  The timed loop issues
+the two sweeps through paro_reduce_shard and paro_adam_shard(dst) - exactly the
+launches paro_step_fused makes when clipping - so that HIP events recorded on
+the launch stream between them give each sweep's own duration; the one-call
+entry point is timed right after as a cross-check.
+
+Prints ONE JSON line.  `value` = shard parameters updated per second.
+`roofline` is for the dominant kernel (sweep 1, the fold): algorithmic bytes
+(2P + 4 per parameter: P bf16 reads, one fp32 write) over its mean duration,
+against 8 TB/s.  `cpu_baseline` times the CPU oracle on a bounded sample of the
+same buffers on this machine's host cores (a baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b_share",
+                    choices=["llama7b_share", "llama65b_share", "tiny_share"])
+    ap.add_argument("--no-clip", action="store_true", help="single-sweep path (max_norm = 0)")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="elements of the shard the oracle is timed on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs, when a
+    summary for this workload has been committed; else None."""
+    path = os.path.join(ROOT, "profiles", f"traffic_k_reduce_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":", 1)[1])
+    return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU's share of the step; it runs on exactly one GPU "
+              f"(got --gpus {args.gpus}).", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2310_06003_amd as paro        # raises if libparo.so has not been built
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    if args.workload == "tiny_share":           # quick functional check of the script itself
+        cfg = wl.Config("tiny_share", 16, 8, "IIG", [16 * 2048 * 64], max_norm=1.0)
+    else:
+        cfg = wl.config(args.workload)
+    P, G, strategy = cfg.P, cfg.G, cfg.strategy
+    rank = 5 if P == 16 else (21 if P == 64 else 0)
+    max_norm = 0.0 if args.no_clip else cfg.max_norm
+    pl = paro.paro_plan(P, G, strategy, cfg.sizes)
+    L = paro.paro_shard_len(pl)
+    ob, ol = paro.paro_range(pl, rank, "O")
+    assert ol == L
+    dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
+
+    contrib = wl.chunk_contribs(P, L, 7, device=dev)
+    p, m, v = wl.master_state(L, 7, device=dev)
+    dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=dev)
+    g = torch.empty(L, dtype=torch.float32, device=dev)
+    ss = torch.zeros(1, dtype=torch.float64, device=dev)
+    ptrs = [t.data_ptr() for t in contrib]
+    hp = dict(wl.ADAM_DEFAULT, grad_scale=1.0 / P, max_norm=max_norm, adamw=True)
+    st = torch.cuda.current_stream().cuda_stream
+
+    def split_step(k, ev=None):
+        hs = paro.make_adam(step=k, **hp)
+        if max_norm > 0:
+            if ev:
+                ev[0].record()
+            paro.paro_reduce_shard(pl, rank, ptrs, paro.PARO_CHUNK, g.data_ptr(), ss.data_ptr(), st)
+            if ev:
+                ev[1].record()
+            paro.paro_adam_shard(pl, rank, hs, g.data_ptr(), ss.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(),
+                                 dst.data_ptr(), st)
+            if ev:
+                ev[2].record()
+        else:
+            if ev:
+                ev[0].record()
+            paro.paro_step_fused(pl, rank, ptrs, paro.PARO_CHUNK, hs, 0, 0, p.data_ptr(), m.data_ptr(), v.data_ptr(),
+                                 dst.data_ptr(), st)
+            if ev:
+                ev[1].record()
+                ev[2].record()
+
+    def fused_step(k):
+        paro.paro_step_fused(pl, rank, ptrs, paro.PARO_CHUNK, paro.make_adam(step=k, **hp), g.data_ptr(),
+                             ss.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(), st)
+
+    K, W = args.steps, args.warmup
+    for k in range(1, W + 1):
+        split_step(k)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        split_step(W + 1 + k, events[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_step = elapsed * 1e3 / K
+    sweep1 = [e[0].elapsed_time(e[1]) for e in events]
+    sweep2 = [e[1].elapsed_time(e[2]) for e in events]
+    ms1, ms2 = float(np.mean(sweep1)), float(np.mean(sweep2))
+
+    # the one-call entry point, same work
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        fused_step(W + K + 1 + k)
+    torch.cuda.synchronize()
+    ms_fused_entry = (time.perf_counter() - t0) * 1e3 / K
+
+    clip = max_norm > 0
+    bytes_step = (2 * P + (34 if clip else 26)) * L
+    bytes_dom = (2 * P + (4 if clip else 26)) * L
+    dom_ms = ms1
+    achieved = bytes_dom / (dom_ms * 1e-3) / 1e9
+    traffic = measured_traffic(args.workload) if clip else None
+    out = {
+        "metric": "shard_params_updated_per_s (fused reduce+Adam+pack step)",
+        "value": L / (ms_step * 1e-3),
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "P": P, "G": G, "strategy": strategy,
+                   "schedule": ["ring", "h-ring", "ho-ring"][paro.paro_sched(pl)], "rank": rank,
+                   "shard_params": L, "contrib_dtype": "bf16", "clip_max_norm": max_norm,
+                   "sweeps": 2 if clip else 1},
+        "hbm_gbps_step": bytes_step / (ms_step * 1e-3) / 1e9,
+        "hbm_frac_step": bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "algorithmic_bytes_per_param_step": 2 * P + (34 if clip else 26),
+        "ms_fused_entry": ms_fused_entry,
+        "kernels": {
+            "sweep1_fold_sumsq": {"ms": ms1, "bytes_per_param": 2 * P + (4 if clip else 26),
+                                  "gbps": bytes_dom / (ms1 * 1e-3) / 1e9},
+        },
+        "roofline": {"kernel": "k_reduce (fold + sum of squares)" if clip else "k_fused (fold + Adam + pack)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic},
+    }
+    if clip:
+        out["kernels"]["sweep2_adam_pack"] = {"ms": ms2, "bytes_per_param": 30, "gbps": 30 * L / (ms2 * 1e-3) / 1e9}
+
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        n = min(args.cpu_sample, L)
+        order, gl = orc.fold_order(P, G, orc.default_sched(P, G), orc.chunk_of_rank(rank, P, G))
+        host = [contrib[q][:n].cpu().view(torch.int16).numpy().view(np.uint16) for q in order]
+        p0, m0, v0 = wl.master_state(n, 7)
+        hp32 = {k: np.float32(x) for k, x in wl.ADAM_DEFAULT.items()}
+
+        def oracle_step(threads, n_el):
+            orc.set_threads(threads)
+            pp, mm, vv = (a[:n_el].numpy().copy() for a in (p0, m0, v0))
+            srcs = [h[:n_el] for h in host]
+            t = time.perf_counter()
+            gg = orc.fold(srcs, gl)
+            tot = orc.sumsq(gg)
+            coef = orc.clip_coef(tot, np.float32(1.0 / P), np.float32(max_norm))
+            orc.adam(gg, pp, mm, vv, sc=float(np.float32(1.0 / P)) * coef, step=1, **hp32)
+            orc.bf16_rne(pp)
+            return n_el / (time.perf_counter() - t)
+
+        nthreads = orc.threads()
+        oracle_step(nthreads, min(n, 1 << 20))                       # page in
+        rate_all = max(oracle_step(nthreads, n) for _ in range(2))
+        n1 = min(n, 1 << 23)
+        rate_one = oracle_step(1, n1)
+        orc.set_threads(nthreads)
+        out["cpu_baseline"] = {"value": rate_all, "unit": "params/s", "cores": nthreads, "kind": "oracle",
+                               "sample": f"first {n} shard elements of the same buffers, all {P} contributions, "
+                                         f"one fused step (fold + sum of squares + clip + Adam fp64 + pack)",
+                               "single_thread": {"value": rate_one, "cores": 1, "sample_elements": n1},
+                               "host_cpus": os.cpu_count()}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -181,16 +181,19 @@ int paro_reduce_shard(paro_plan_t *plan, int rank, const void *const *contrib, i
 
 /* Adam over the update range, in place on p, m, v.  total_sumsq: DEVICE double
  * = the sum over all ranks of their sumsq_out (read when hp->max_norm > 0; may
- * be NULL otherwise). */
+ * be NULL otherwise).  dst_base: NULL, or the buffer of paro_pack_params - then
+ * the updated parameters are also packed, in the same sweep. */
 int paro_adam_shard(paro_plan_t *plan, int rank, const paro_adam_t *hp, const float *grad,
-                    const double *total_sumsq, float *p, float *m, float *v, void *stream);
+                    const double *total_sumsq, float *p, float *m, float *v, uint16_t *dst_base,
+                    void *stream);
 
 /* dst_base[slot_off + e] = bf16(p[e]), round to nearest even, over the update
  * range.  dst_base: DEVICE uint16 array of dst_len elements (paro_pack_slot),
  * 16-byte aligned. */
 int paro_pack_params(paro_plan_t *plan, int rank, const float *p, uint16_t *dst_base, void *stream);
 
-/* reduce + clip + Adam + pack.  With hp->max_norm > 0: sweep 1 writes the
+/* reduce + clip + Adam + pack.  With hp->max_norm > 0 it is exactly
+ * paro_reduce_shard followed by paro_adam_shard with dst_base: sweep 1 writes the
  * reduced gradient to grad_scratch (DEVICE fp32 over the update range) and the
  * sum of squares to *sumsq_scratch (DEVICE double); sweep 2 clips with THIS
  * rank's sum of squares as the total (a single-rank norm: the cross-rank sum a

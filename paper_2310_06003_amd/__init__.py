@@ -74,7 +74,7 @@ EXPORTS = {
     "paro_pack_slot": (c_int, [c_void_p, c_int, POINTER(c_int64), POINTER(c_int64), POINTER(c_int64)]),
     "paro_reduce_shard": (c_int, [c_void_p, c_int, POINTER(c_void_p), c_int, c_void_p, c_void_p, c_void_p]),
     "paro_adam_shard": (c_int, [c_void_p, c_int, POINTER(paro_adam_t), c_void_p, c_void_p, c_void_p, c_void_p,
-                                c_void_p, c_void_p]),
+                                c_void_p, c_void_p, c_void_p]),
     "paro_pack_params": (c_int, [c_void_p, c_int, c_void_p, c_void_p, c_void_p]),
     "paro_step_fused": (c_int, [c_void_p, c_int, POINTER(c_void_p), c_int, POINTER(paro_adam_t), c_void_p, c_void_p,
                                 c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
@@ -208,8 +208,8 @@ def paro_reduce_shard(plan: Plan, rank: int, contrib: Sequence[int], layout: int
 
 
 def paro_adam_shard(plan: Plan, rank: int, hp: paro_adam_t, grad: int, total_sumsq: int, p: int, m: int, v: int,
-                    stream: int = 0) -> None:
-    _check(_lib.paro_adam_shard(plan.handle, rank, byref(hp), grad, total_sumsq, p, m, v, stream))
+                    dst_base: int = 0, stream: int = 0) -> None:
+    _check(_lib.paro_adam_shard(plan.handle, rank, byref(hp), grad, total_sumsq, p, m, v, dst_base, stream))
 
 
 def paro_pack_params(plan: Plan, rank: int, p: int, dst_base: int, stream: int = 0) -> None:

@@ -761,7 +761,7 @@ int paro_reduce_shard(paro_plan_t *pl, int rank, const void *const *contrib, int
 }
 
 int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const float *grad, const double *total_sumsq,
-                    float *p, float *m, float *v, void *stream) {
+                    float *p, float *m, float *v, uint16_t *dst_base, void *stream) {
     int rc;
     AdamConsts a;
     if ((rc = check_common(pl, rank, "paro_adam_shard"))) return rc;
@@ -772,8 +772,16 @@ int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const floa
     if ((rc = check_ptr(v, "paro_adam_shard: v"))) return rc;
     if (a.max_norm > 0.0f && !total_sumsq)
         return fail(PARO_EINVAL, "paro_adam_shard: clipping needs total_sumsq");
+    if (dst_base && (reinterpret_cast<uintptr_t>(dst_base) & 15))
+        return fail(PARO_EALIGN, "paro_adam_shard: dst_base is not 16-byte aligned");
     if ((rc = ensure_device(pl))) return rc;
-    return do_adam(pl, rank, a, grad, total_sumsq, p, m, v, nullptr, static_cast<hipStream_t>(stream));
+    uint16_t *dst = nullptr;
+    if (dst_base) {
+        int64_t dl, so, sl;
+        paro_pack_slot(pl, rank, &dl, &so, &sl);
+        dst = dst_base + so;
+    }
+    return do_adam(pl, rank, a, grad, total_sumsq, p, m, v, dst, static_cast<hipStream_t>(stream));
 }
 
 int paro_pack_params(paro_plan_t *pl, int rank, const float *p, uint16_t *dst_base, void *stream) {

@@ -49,11 +49,20 @@ class PtrTable:
         return self.table.data_ptr()
 
 
-def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None):
-    """gpu / ref: dicts with p, m, v (fp32 numpy) and q (uint16 bf16 bits)."""
+def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None, hist=None, literal=None):
+    """gpu / ref: dicts with p, m, v (fp32 numpy) and q (uint16 bf16 bits).  ref is the
+    fp64 evaluation (the 1e-6 contract).  literal, when given, is the oracle's all-fp32
+    evaluation in the kernel's operation order: IEEE arithmetic leaves no freedom there,
+    so it must match bit for bit."""
     check_moments_and_params(gpu["p"], gpu["m"], gpu["v"], ref["p"], ref["m"], ref["v"], p_old=p_old, m_old=m_old,
-                             g_hat=g_hat, what=what)
+                             g_hat=g_hat, what=what, hist=hist)
     check_bf16_within_one_ulp(gpu["q"], ref["q"], what)
+    if literal is not None:
+        for k in ("p", "m", "v", "q"):
+            a, b = gpu[k], literal[k]
+            if k != "q":        # +0 and -0 are the same value (they differ only for masked-out weight decay)
+                a, b = a + np.float32(0), b + np.float32(0)
+            assert a.tobytes() == b.tobytes(), f"{what}: {k} differs from the fp32-literal oracle"
     if report is not None:
         report.append((what, ulp_distance_f32(gpu["p"], ref["p"]), ulp_distance_f32(gpu["v"], ref["v"])))
 

@@ -12,16 +12,24 @@ REL = 1e-6
 
 
 def check_moments_and_params(got_p, got_m, got_v, ref_p, ref_m, ref_v, *, p_old, m_old, g_hat,
-                             beta1=0.9, what=""):
+                             beta1=0.9, what="", hist=None):
     """All arrays fp32 (got_*: path under test; ref_*: fp64 evaluation rounded once);
-    g_hat = scaled, clipped gradient as fp64."""
+    g_hat = scaled, clipped gradient as fp64.  In a run of several steps each side
+    carries its own state, so a rounding made when the terms were large is still
+    there after they have cancelled: pass the same dict as `hist` at every step and
+    the term magnitudes become running maxima over the run."""
     b1 = float(np.float32(beta1))
     ref_p64, ref_m64, ref_v64 = (a.astype(np.float64) for a in (ref_p, ref_m, ref_v))
     floor_m = np.abs(b1 * m_old.astype(np.float64)) + np.abs((1 - b1) * g_hat)
-    tol_m = REL * np.maximum(np.abs(ref_m64), floor_m)
     tol_v = REL * np.abs(ref_v64)
     floor_p = np.abs(p_old.astype(np.float64)) + np.abs(ref_p64 - p_old.astype(np.float64))
-    tol_p = REL * np.maximum(np.abs(ref_p64), floor_p)
+    floor_p = np.maximum(np.abs(ref_p64), floor_p)
+    floor_m = np.maximum(np.abs(ref_m64), floor_m)
+    if hist is not None:
+        floor_p = hist["p"] = np.maximum(hist.get("p", 0.0), floor_p)
+        floor_m = hist["m"] = np.maximum(hist.get("m", 0.0), floor_m)
+    tol_p = REL * floor_p
+    tol_m = REL * floor_m
     for name, got, ref, tol in (("m", got_m, ref_m64, tol_m), ("v", got_v, ref_v64, tol_v),
                                 ("p", got_p, ref_p64, tol_p)):
         bad = np.abs(got.astype(np.float64) - ref) > tol

@@ -1,0 +1,170 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration the
+benchmark times.
+
+Llama-7B share (P=16, G=8, IIG, 421 M shard params): the oracle streams the whole
+shard in blocks, so the reduced gradient and the sum of squares are checked in
+full; Adam and the pack are checked on sampled blocks (elements are independent,
+so a block check is exact).
+
+65B share (P=64, G=8, IGG, 1.02 G shard params, two-level HO-Ring order): the
+oracle folds sampled blocks only (the full fold would move 130 GB to the host);
+the sum of squares is checked against an fp64 reduction of the verified
+gradient, and Adam + pack run with a norm total supplied by the harness, as a
+cross-rank sum would supply it."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import workloads as wl
+from harness import DEV, compare_step, hp_dict, hp_struct, np_of, oracle_update, stream
+
+pytestmark = pytest.mark.gpu
+
+BLOCK = 1 << 24
+
+
+def _need_memory(gib):
+    free, _ = torch.cuda.mem_get_info()
+    if free < gib * (1 << 30):
+        pytest.skip(f"needs {gib} GiB of free device memory")
+
+
+def _sample_blocks(L, block, n_random, seed):
+    nb = (L + block - 1) // block
+    rng = np.random.default_rng(seed)
+    picks = {0, nb - 1} | {int(x) for x in rng.integers(0, nb, n_random)}
+    return [(b * block, min(block, L - b * block)) for b in sorted(picks)]
+
+
+def test_llama7b_share_full_size(paro):
+    _need_memory(40)
+    cfg = wl.config("llama7b_share")
+    P, G, strategy, rank = cfg.P, cfg.G, cfg.strategy, 5
+    lay = orc.layout(P, G, cfg.sizes)
+    L = lay.L
+    assert L == 421_150_976 and lay.total == 6_738_415_616
+    sched = orc.default_sched(P, G)
+    assert sched == orc.HORING
+    pl = paro.paro_plan(P, G, strategy, cfg.sizes)
+    order, gl = orc.fold_order(P, G, sched, orc.chunk_of_rank(rank, P, G))
+
+    contrib = wl.chunk_contribs(P, L, 7, device=DEV)
+    p, m, v = wl.master_state(L, 7, device=DEV)
+    picks = _sample_blocks(L, BLOCK, 5, seed=1)
+    old = {lo: [np_of(t[lo:lo + n]) for t in (p, m, v)] for lo, n in picks}
+
+    dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
+    assert (dst_len, slot_off, slot_len) == orc.pack_slot(lay, rank, strategy) == (2 * L, 0, L)
+    dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+    g = torch.empty(L, dtype=torch.float32, device=DEV)
+    ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+    hp = hp_dict(P, max_norm=cfg.max_norm)
+    paro.paro_step_fused(pl, rank, [t.data_ptr() for t in contrib], paro.PARO_CHUNK, hp_struct(paro, hp, 1),
+                         g.data_ptr(), ss.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(),
+                         stream())
+    torch.cuda.synchronize()
+
+    # the oracle streams the shard: full parity of the reduced gradient, full sum of squares
+    total_ref = 0.0
+    g_blocks = {}
+    for lo in range(0, L, BLOCK):
+        n = min(BLOCK, L - lo)
+        gr = orc.fold([np_of(contrib[q][lo:lo + n]) for q in order], gl)
+        assert np_of(g[lo:lo + n]).tobytes() == gr.tobytes(), f"reduced gradient differs in block at {lo}"
+        total_ref += orc.sumsq(gr)
+        if lo in old:
+            g_blocks[lo] = gr
+    assert abs(float(ss.item()) - total_ref) <= 1e-12 * total_ref
+    coef = orc.clip_coef(total_ref, np.float32(hp["grad_scale"]), np.float32(hp["max_norm"]))
+    assert coef < 1.0
+    print(f"\n[llama7b share] sum of squares {total_ref:.6e}, clip coefficient {coef:.6f}")
+
+    for lo, n in picks:
+        p0, m0, v0 = old[lo]
+        ref = oracle_update(lay, strategy, rank, g_blocks[lo], p0, m0, v0, total_sumsq=total_ref, hp=hp, step=1)
+        lit = oracle_update(lay, strategy, rank, g_blocks[lo], p0, m0, v0, total_sumsq=total_ref, hp=hp, step=1,
+                            literal32=True)
+        got = dict(p=np_of(p[lo:lo + n]), m=np_of(m[lo:lo + n]), v=np_of(v[lo:lo + n]),
+                   q=np_of(dst[slot_off + lo:slot_off + lo + n]))
+        g_hat = float(np.float32(hp["grad_scale"])) * coef * g_blocks[lo].astype(np.float64)
+        compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"llama7b block at {lo}", literal=lit)
+    assert not bool(dst[L:].any()), "the other group's slot of the parameter block must stay untouched"
+
+
+def test_llama65b_share_full_size(paro):
+    _need_memory(200)
+    cfg = wl.config("llama65b_share")
+    P, G, strategy = cfg.P, cfg.G, cfg.strategy
+    rank = 21                                   # group 2, local index 5
+    lay = orc.layout(P, G, cfg.sizes)
+    L = lay.L
+    assert L == 1_020_088_448 and lay.total == 65_285_660_672
+    sched = orc.default_sched(P, G)
+    pl = paro.paro_plan(P, G, strategy, cfg.sizes)
+    order, gl = orc.fold_order(P, G, sched, orc.chunk_of_rank(rank, P, G))
+    assert gl == G and order[-1] == rank and paro.paro_fold_order(pl, orc.chunk_of_rank(rank, P, G)) == (order, gl)
+
+    contrib = wl.chunk_contribs(P, L, 9, device=DEV)
+    p, m, v = wl.master_state(L, 9, device=DEV)
+    blk = 1 << 22
+    picks = _sample_blocks(L, blk, 4, seed=2)
+    old = {lo: [np_of(t[lo:lo + n]) for t in (p, m, v)] for lo, n in picks}
+    dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
+    assert (dst_len, slot_off, slot_len) == (8 * L, 2 * L, L)          # sub-slot j = 2 of the group block
+    dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+    g = torch.empty(L, dtype=torch.float32, device=DEV)
+    ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ptrs = [t.data_ptr() for t in contrib]
+
+    paro.paro_reduce_shard(pl, rank, ptrs, paro.PARO_CHUNK, g.data_ptr(), ss.data_ptr(), stream())
+    torch.cuda.synchronize()
+    g_blocks = {}
+    for lo, n in picks:
+        gr = orc.fold([np_of(contrib[q][lo:lo + n]) for q in order], gl)
+        assert np_of(g[lo:lo + n]).tobytes() == gr.tobytes(), f"reduced gradient differs in block at {lo}"
+        g_blocks[lo] = gr
+    # property: the scalar is the sum of squares of the (sample-verified) gradient
+    chk = 0.0
+    for lo in range(0, L, 1 << 27):
+        chk += float(g[lo:lo + (1 << 27)].double().square().sum().item())
+    assert abs(float(ss.item()) - chk) <= 1e-11 * chk
+
+    # Adam + pack with a total as a cross-rank sum would deliver it (64 shards of about this size)
+    total = 64 * 65000.0
+    hp = hp_dict(P, max_norm=cfg.max_norm)
+    tot = torch.tensor([total], dtype=torch.float64, device=DEV)
+    paro.paro_adam_shard(pl, rank, hp_struct(paro, hp, 1), g.data_ptr(), tot.data_ptr(), p.data_ptr(), m.data_ptr(),
+                         v.data_ptr(), dst.data_ptr(), stream())
+    torch.cuda.synchronize()
+    coef = orc.clip_coef(total, np.float32(hp["grad_scale"]), np.float32(hp["max_norm"]))
+    assert coef < 1.0
+    for lo, n in picks:
+        p0, m0, v0 = old[lo]
+        ref = oracle_update(lay, strategy, rank, g_blocks[lo], p0, m0, v0, total_sumsq=total, hp=hp, step=1)
+        lit = oracle_update(lay, strategy, rank, g_blocks[lo], p0, m0, v0, total_sumsq=total, hp=hp, step=1,
+                            literal32=True)
+        got = dict(p=np_of(p[lo:lo + n]), m=np_of(m[lo:lo + n]), v=np_of(v[lo:lo + n]),
+                   q=np_of(dst[slot_off + lo:slot_off + lo + n]))
+        g_hat = float(np.float32(hp["grad_scale"])) * coef * g_blocks[lo].astype(np.float64)
+        compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"llama65b block at {lo}", literal=lit)
+
+    # the single-sweep path (no clipping) at P = 64, from the same starting state, on the samples
+    del g
+    p2, m2, v2 = wl.master_state(L, 9, device=DEV)
+    hp2 = hp_dict(P, max_norm=0.0)
+    dst.zero_()
+    paro.paro_step_fused(pl, rank, ptrs, paro.PARO_CHUNK, hp_struct(paro, hp2, 1), 0, 0, p2.data_ptr(),
+                         m2.data_ptr(), v2.data_ptr(), dst.data_ptr(), stream())
+    torch.cuda.synchronize()
+    for lo, n in picks:
+        p0, m0, v0 = old[lo]
+        ref = oracle_update(lay, strategy, rank, g_blocks[lo], p0, m0, v0, total_sumsq=0.0, hp=hp2, step=1)
+        lit = oracle_update(lay, strategy, rank, g_blocks[lo], p0, m0, v0, total_sumsq=0.0, hp=hp2, step=1,
+                            literal32=True)
+        got = dict(p=np_of(p2[lo:lo + n]), m=np_of(m2[lo:lo + n]), v=np_of(v2[lo:lo + n]),
+                   q=np_of(dst[slot_off + lo:slot_off + lo + n]))
+        g_hat = float(np.float32(hp2["grad_scale"])) * g_blocks[lo].astype(np.float64)
+        compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"llama65b single sweep, block at {lo}",
+                     literal=lit)
+    assert not bool(dst[:slot_off].any()) and not bool(dst[slot_off + L:].any())

@@ -37,6 +37,7 @@ def _run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, step, 
     p0, m0, v0 = (a[ob:ob + ol].copy() for a in state)
     total = ss_ref
     ref = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=step)
+    lit = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=step, literal32=True)
     g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
 
     dst_len, slot_off, slot_len = orc.pack_slot(lay, rank, strategy)
@@ -55,7 +56,7 @@ def _run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, step, 
                          stream())
     q_all = np_of(dst)
     fused = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=q_all[slot_off:slot_off + slot_len])
-    compare_step(fused, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=what + " fused", report=report)
+    compare_step(fused, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=what + " fused", report=report, literal=lit)
     assert (fused["q"] == orc.bf16_rne(fused["p"])).all(), what + ": pack is not the rounding of the stored p"
     assert not q_all[:slot_off].any() and not q_all[slot_off + slot_len:].any(), what + ": wrote outside the slot"
     if hp["max_norm"] > 0:
@@ -66,7 +67,7 @@ def _run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, step, 
         dst2 = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
         tot = torch.tensor([total], dtype=torch.float64, device=DEV)
         paro.paro_adam_shard(pl, rank, hp_struct(paro, hp, step), g.data_ptr(), tot.data_ptr(), p.data_ptr(),
-                             m.data_ptr(), v.data_ptr(), stream())
+                             m.data_ptr(), v.data_ptr(), 0, stream())
         paro.paro_pack_params(pl, rank, p.data_ptr(), dst2.data_ptr(), stream())
         for name, t in (("p", p), ("m", m), ("v", v)):
             assert np_of(t).tobytes() == fused[name].tobytes(), what + f": unfused {name} differs from fused"
@@ -250,6 +251,8 @@ def test_tensor_layout_small_ragged(paro):
             # every rank keeps its own copy of its range on both sides (replicas of a range clip with
             # their own rank's norm here, so they may drift apart - as they would on the GPU side)
             ora_state = [[a[slice(*_rng(lay, r, strategy))].copy() for a in state] for r in range(P)]
+            lit_state = [[a.copy() for a in st] for st in ora_state]
+            hist = [dict() for _ in range(P)]
             gpu_state = [[torch.from_numpy(a.copy()).to(DEV) for a in ora_state[r]] for r in range(P)]
             for step in (1, 2):
                 sets = wl.tensor_contribs(P, sizes, dtypes, 60, step, device=DEV, align_elems=align)
@@ -261,6 +264,8 @@ def test_tensor_layout_small_ragged(paro):
                     old = ora_state[rank]
                     ref = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=step,
                                         no_decay=no_decay)
+                    lit = oracle_update(lay, strategy, rank, g_ref, *lit_state[rank], total_sumsq=ss_ref, hp=hp,
+                                        step=step, no_decay=no_decay, literal32=True)
                     p, m, v = gpu_state[rank]
                     dst_len, slot_off, slot_len = orc.pack_slot(lay, rank, strategy)
                     dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
@@ -276,8 +281,10 @@ def test_tensor_layout_small_ragged(paro):
                         assert ref["coef"] < 1.0
                     g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
                     got = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=np_of(dst)[slot_off:slot_off + slot_len])
-                    compare_step(got, ref, p_old=old[0], m_old=old[1], g_hat=g_hat, what=what)
+                    compare_step(got, ref, p_old=old[0], m_old=old[1], g_hat=g_hat, what=what, hist=hist[rank],
+                                 literal=lit)
                     ora_state[rank] = [ref["p"], ref["m"], ref["v"]]
+                    lit_state[rank] = [lit["p"], lit["m"], lit["v"]]
 
 
 def _rng(lay, rank, strategy):

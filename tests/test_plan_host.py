@@ -127,12 +127,13 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(paro):
     assert code(paro.paro_reduce_shard, pl, 0, [ok] * 4, 5, ok, ok) == paro.PARO_EINVAL
     assert code(paro.paro_reduce_shard, pl, 0, [ok] * 4, paro.PARO_CHUNK, ok + 4, ok) == paro.PARO_EALIGN
     assert code(paro.paro_reduce_shard, pl, 0, [ok] * 4, paro.PARO_CHUNK, 0, ok) == paro.PARO_EINVAL
-    assert code(paro.paro_adam_shard, pl, 0, hp, ok, 0, ok, ok + 8, ok) == paro.PARO_EALIGN
+    assert code(paro.paro_adam_shard, pl, 0, hp, ok, 0, ok, ok + 8, ok, 0) == paro.PARO_EALIGN
     hp_clip = paro.make_adam(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, grad_scale=0.25,
                              max_norm=1.0)
-    assert code(paro.paro_adam_shard, pl, 0, hp_clip, ok, 0, ok, ok, ok) == paro.PARO_EINVAL
+    assert code(paro.paro_adam_shard, pl, 0, hp_clip, ok, 0, ok, ok, ok, 0) == paro.PARO_EINVAL
     hp_bad = paro.make_adam(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, grad_scale=0.25, step=0)
-    assert code(paro.paro_adam_shard, pl, 0, hp_bad, ok, 0, ok, ok, ok) == paro.PARO_EINVAL
+    assert code(paro.paro_adam_shard, pl, 0, hp_bad, ok, 0, ok, ok, ok, 0) == paro.PARO_EINVAL
+    assert code(paro.paro_adam_shard, pl, 0, hp, ok, 0, ok, ok, ok, ok + 2) == paro.PARO_EALIGN
     assert code(paro.paro_pack_params, pl, 0, ok, ok + 2) == paro.PARO_EALIGN
     assert code(paro.paro_step_fused, pl, 0, [ok] * 4, paro.PARO_CHUNK, hp_clip, 0, ok, ok, ok, ok, ok) == paro.PARO_EINVAL
     mixed = paro.paro_plan(4, 2, "IIG", [64, 64], grad_dtype=[0, 1])
