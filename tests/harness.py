@@ -54,9 +54,9 @@ def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None, hist=None,
     fp64 evaluation (the 1e-6 contract).  literal, when given, is the oracle's all-fp32
     evaluation in the kernel's operation order: IEEE arithmetic leaves no freedom there,
     so it must match bit for bit."""
-    check_moments_and_params(gpu["p"], gpu["m"], gpu["v"], ref["p"], ref["m"], ref["v"], p_old=p_old, m_old=m_old,
-                             g_hat=g_hat, what=what, hist=hist)
-    check_bf16_within_one_ulp(gpu["q"], ref["q"], what)
+    tol_p = check_moments_and_params(gpu["p"], gpu["m"], gpu["v"], ref["p"], ref["m"], ref["v"], p_old=p_old,
+                                     m_old=m_old, g_hat=g_hat, what=what, hist=hist)
+    check_bf16_within_one_ulp(gpu["q"], ref["q"], what, ref_p=ref["p"], tol_p=tol_p)
     if literal is not None:
         for k in ("p", "m", "v", "q"):
             a, b = gpu[k], literal[k]
