@@ -12,6 +12,12 @@ import os
 from ctypes import POINTER, Structure, byref, c_char, c_char_p, c_float, c_int, c_int32, c_int64, c_uint8, c_void_p
 from typing import List, Optional, Sequence, Tuple
 
+# The caller's device buffers and streams come from PyTorch, which ships its own copy of the HIP
+# runtime.  A process must run on ONE runtime: load torch's first, so that libparo.so's dependency on
+# libamdhip64 binds to the copy that owns those buffers and streams (a second, separately loaded
+# runtime sees no device).
+import torch  # noqa: F401  (imported for its side effect on the loader)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SO = os.path.join(_HERE, "libparo.so")
 
