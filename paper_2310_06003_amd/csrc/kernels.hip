@@ -28,10 +28,36 @@
 
 namespace {
 
-constexpr int TPB = 256;            // threads per block
+// Launch-shape and cache-policy knobs (the defaults are the measured best on MI355X).
+#ifndef PARO_NT_FOLD
+#define PARO_NT_FOLD 1              // streaming (non-temporal) loads for the contributions
+#endif
+#ifndef PARO_NT_STATE
+#define PARO_NT_STATE 0             // ... for g, p, m, v
+#endif
+#ifndef PARO_NT_GSTORE
+#define PARO_NT_GSTORE 1            // ... stores of the reduced gradient in sweep 1
+#endif
+#ifndef PARO_TPBK_FOLD
+#define PARO_TPBK_FOLD 4            // 0: persistent grid-stride blocks; k > 0: block b takes tiles [b*k, b*k + k)
+#endif
+#ifndef PARO_TPBK_ADAM
+#define PARO_TPBK_ADAM 1
+#endif
+#ifndef PARO_BLOCKS_PER_CU
+#define PARO_BLOCKS_PER_CU 8
+#endif
+#ifndef PARO_BATCH_BF16
+#define PARO_BATCH_BF16 16
+#endif
+#ifndef PARO_TPB
+#define PARO_TPB 256
+#endif
+
+constexpr int TPB = PARO_TPB;        // threads per block
 constexpr int EPT = 8;              // elements per thread per tile
-constexpr int TILE = TPB * EPT;     // 2048
-constexpr int BLOCKS_PER_CU = 8;
+constexpr int TILE = TPB * EPT;     // 2048 with 256 threads
+constexpr int BLOCKS_PER_CU = PARO_BLOCKS_PER_CU;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -67,17 +93,35 @@ __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+template <bool NT, class V>
+__device__ __forceinline__ V ld_as(const V *p) {
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <class V>
+__device__ __forceinline__ V ld_contrib(const V *p) { return ld_as<PARO_NT_FOLD != 0>(p); }
+template <class V>
+__device__ __forceinline__ V ld_state(const V *p) { return ld_as<PARO_NT_STATE != 0>(p); }
+template <bool NT, class V>
+__device__ __forceinline__ void st_as(V *p, V v) {
+    if (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
 __device__ __forceinline__ void load8_f32(const float *p, float x[8]) {
-    f32x4 a = *reinterpret_cast<const f32x4 *>(p);
-    f32x4 b = *reinterpret_cast<const f32x4 *>(p + 4);
+    f32x4 a = ld_state(reinterpret_cast<const f32x4 *>(p));
+    f32x4 b = ld_state(reinterpret_cast<const f32x4 *>(p + 4));
     x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
     x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
 }
 
+template <bool NT = false>
 __device__ __forceinline__ void store8_f32(float *p, const float x[8]) {
     f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
-    *reinterpret_cast<f32x4 *>(p) = a;
-    *reinterpret_cast<f32x4 *>(p + 4) = b;
+    st_as<NT>(reinterpret_cast<f32x4 *>(p), a);
+    st_as<NT>(reinterpret_cast<f32x4 *>(p + 4), b);
 }
 
 __device__ __forceinline__ void store8_bf16(uint16_t *p, const float x[8]) {
@@ -122,17 +166,17 @@ template <int DT>
 struct ChunkLoader {
     static constexpr bool kTensor = false;
     // contributions loaded before the first is consumed (16 bytes each for bf16, 32 for fp32)
-    static constexpr int kBatch = DT == PARO_BF16 ? 16 : 8;
+    static constexpr int kBatch = DT == PARO_BF16 ? PARO_BATCH_BF16 : 8;
     struct Raw { u32x4 a, b; };
     int64_t e;                                   // first of the thread's 8 elements
     __device__ __forceinline__ void prepare(int64_t e0, const Where8 &) { e = e0; }
     __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
         if (DT == PARO_BF16) {
-            r.a = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(src.p[k]) + e);
+            r.a = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(src.p[k]) + e));
         } else {
             const u32x4 *q = reinterpret_cast<const u32x4 *>(static_cast<const float *>(src.p[k]) + e);
-            r.a = q[0];
-            r.b = q[1];
+            r.a = ld_contrib(q);
+            r.b = ld_contrib(q + 1);
         }
     }
     __device__ __forceinline__ void unpack(const Raw &r, float x[8]) const {
@@ -255,7 +299,7 @@ struct TensorLoader {
             const char *base = static_cast<const char *>(ptrs[t]) + w->toff[0] * (is_bf16 ? 2 : 4);
             if ((reinterpret_cast<uintptr_t>(base) & 15) == 0) {
                 if (is_bf16) {
-                    u32x4 q = *reinterpret_cast<const u32x4 *>(base);
+                    u32x4 q = ld_contrib(reinterpret_cast<const u32x4 *>(base));
                     r.x[0] = bf16_lo(q.x); r.x[1] = bf16_hi(q.x); r.x[2] = bf16_lo(q.y); r.x[3] = bf16_hi(q.y);
                     r.x[4] = bf16_lo(q.z); r.x[5] = bf16_hi(q.z); r.x[6] = bf16_lo(q.w); r.x[7] = bf16_hi(q.w);
                 } else {
@@ -370,6 +414,14 @@ __device__ __forceinline__ void adam1(const AdamConsts &a, float sc, bool decays
     }
 }
 
+// Which tiles a block takes: TPBK == 0: grid-stride (persistent blocks); TPBK > 0: a run of
+// TPBK consecutive tiles.
+#define TILE_LOOP(TPBK, tile, ntiles)                                                                       \
+    for (int64_t tile = (TPBK) ? (int64_t)blockIdx.x * (TPBK) : (int64_t)blockIdx.x,                        \
+                 tile##_end = (TPBK) ? min((int64_t)(ntiles), tile + (TPBK)) : (int64_t)(ntiles),           \
+                 tile##_step = (TPBK) ? 1 : (int64_t)gridDim.x;                                             \
+         tile < tile##_end; tile += tile##_step)
+
 // --------------------------------------------------------------------- kernels
 // Sweep 1: g = fold of the contributions; optional per-block partial of sum g^2.
 template <class Ld, bool SUMSQ>
@@ -382,7 +434,7 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
     segs.s_head = s_head;
     double acc = 0.0;
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles) {
         if (Ld::kTensor) segs.begin_tile(tile * TILE);
         const int rel0 = threadIdx.x * EPT;
         const int64_t e = tile * TILE + rel0;
@@ -392,7 +444,7 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
             ld.prepare(e, w);
             float X[8];
             fold8(ld, src, P, group_len, X);
-            store8_f32(g + e, X);
+            store8_f32<PARO_NT_GSTORE != 0>(g + e, X);
             if (SUMSQ) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc += (double)X[i] * (double)X[i];
@@ -427,7 +479,7 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
     segs.s_head = s_head;
     const float sc = scale_from_norm(a, total_sumsq);
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles) {
         if (MASK) segs.begin_tile(tile * TILE);
         const int rel0 = threadIdx.x * EPT;
         const int64_t e = tile * TILE + rel0;
@@ -470,7 +522,7 @@ __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P,
     segs.s_head = s_head;
     const float sc = a.grad_scale;                     // no clipping on this path
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles) {
         if (NEED_SEGS) segs.begin_tile(tile * TILE);
         const int rel0 = threadIdx.x * EPT;
         const int64_t e = tile * TILE + rel0;
@@ -500,7 +552,7 @@ __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P,
 // bf16 pack alone.
 __global__ __launch_bounds__(TPB) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n) {
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles) {
         const int64_t e = tile * TILE + threadIdx.x * EPT;
         if (e < n) {
             float pp[8];
@@ -556,14 +608,22 @@ int ensure_device(paro_plan_t *pl) {
     if ((rc = upload(&d.nz_tensor, pl->nz_tensor.data(), pl->nz_tensor.size()))) return rc;
     if ((rc = upload(&d.dtype, pl->dtype.data(), pl->dtype.size()))) return rc;
     if ((rc = upload(&d.no_decay, pl->no_decay.data(), pl->no_decay.size()))) return rc;
-    PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), PARO_MAX_PARTIALS * sizeof(double)));
+    // one partial per block of the largest sweep-1 launch (a launch covers one chunk of L elements)
+    int64_t n_part = (pl->L + TILE - 1) / TILE;
+    if (n_part < PARO_MAX_PARTIALS) n_part = PARO_MAX_PARTIALS;
+    PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), n_part * sizeof(double)));
     d.device = dev;
     pl->dev = d;
     return PARO_OK;
 }
 
-int grid_for(const paro_plan_t *pl, int64_t n) {
+// Blocks of a launch over n elements, for a kernel that takes tpbk tiles per block (0 = persistent).
+int grid_for(const paro_plan_t *pl, int64_t n, int tpbk) {
     const int64_t ntiles = (n + TILE - 1) / TILE;
+    if (tpbk > 0) {
+        const int64_t nb = (ntiles + tpbk - 1) / tpbk;
+        return (int)(nb < 1 ? 1 : nb);
+    }
     int64_t cap = (int64_t)pl->dev.n_cu * BLOCKS_PER_CU;
     if (cap > PARO_MAX_PARTIALS) cap = PARO_MAX_PARTIALS;
     return (int)(ntiles < cap ? (ntiles < 1 ? 1 : ntiles) : cap);
@@ -648,7 +708,7 @@ template <bool SUMSQ>
 void launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t flat_begin, float *g,
                    hipStream_t st) {
     const int64_t n = pl->L;
-    const int grid = grid_for(pl, n);
+    const int grid = grid_for(pl, n, PARO_TPBK_FOLD);
     TileSegs segs = segs_for(pl, flat_begin);
     double *partials = pl->dev.partials;
     if (layout == PARO_TENSORS) {
@@ -670,7 +730,7 @@ template <bool MASK>
 void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t flat_begin,
                   const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
-    const int grid = grid_for(pl, n);
+    const int grid = grid_for(pl, n, PARO_TPBK_FOLD);
     TileSegs segs = segs_for(pl, flat_begin);
     if (layout == PARO_TENSORS) {
         TensorLoader ld{pl->dev.dtype, nullptr};
@@ -706,7 +766,7 @@ int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout,
         PARO_HIP(hipGetLastError());
     }
     if (sumsq_out) {
-        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(TPB), 0, st, pl->dev.partials, grid_for(pl, pl->L), sumsq_out);
+        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(TPB), 0, st, pl->dev.partials, grid_for(pl, pl->L, PARO_TPBK_FOLD), sumsq_out);
         PARO_HIP(hipGetLastError());
     }
     return PARO_OK;
@@ -716,7 +776,7 @@ int do_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, c
             float *m, float *v, uint16_t *dst /* nullable: no pack */, hipStream_t st) {
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
-    const int grid = grid_for(pl, on);
+    const int grid = grid_for(pl, on, PARO_TPBK_ADAM);
     TileSegs segs = segs_for(pl, ob);
     const bool mask = pl->any_no_decay;
     if (dst && mask)
@@ -792,7 +852,7 @@ int paro_pack_params(paro_plan_t *pl, int rank, const float *p, uint16_t *dst_ba
     if ((rc = ensure_device(pl))) return rc;
     int64_t dl, so, sl;
     paro_pack_slot(pl, rank, &dl, &so, &sl);
-    hipLaunchKernelGGL(k_pack, dim3(grid_for(pl, sl)), dim3(TPB), 0, static_cast<hipStream_t>(stream), p,
+    hipLaunchKernelGGL(k_pack, dim3(grid_for(pl, sl, PARO_TPBK_ADAM)), dim3(TPB), 0, static_cast<hipStream_t>(stream), p,
                        dst_base + so, sl);
     PARO_HIP(hipGetLastError());
     return PARO_OK;
