@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-clip", action="store_true", help="single-sweep path (max_norm = 0)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="elements of the shard the oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-ref", action="store_true",
+                    help="only run a plain 4 GiB device copy three times (reference for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     return ap.parse_args()
 
 
@@ -70,6 +73,17 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.copy_ref:
+        n = (4 << 30) // 4
+        a = torch.ones(n, dtype=torch.float32, device=dev)
+        b = torch.zeros(n, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_ref_bytes_read": 4 << 30, "copy_ref_bytes_written": 4 << 30, "launches": 3}))
+        return
 
     if args.workload == "tiny_share":           # quick functional check of the script itself
         cfg = wl.Config("tiny_share", 16, 8, "IIG", [16 * 2048 * 64], max_norm=1.0)

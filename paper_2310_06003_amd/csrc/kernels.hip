@@ -39,10 +39,16 @@ namespace {
 #define PARO_NT_GSTORE 1            // ... stores of the reduced gradient in sweep 1
 #endif
 #ifndef PARO_TPBK_FOLD
-#define PARO_TPBK_FOLD 4            // 0: persistent grid-stride blocks; k > 0: block b takes tiles [b*k, b*k + k)
+#define PARO_TPBK_FOLD 2            // 0: persistent grid-stride blocks; k > 0: block b takes tiles [b*k, b*k + k)
 #endif
 #ifndef PARO_TPBK_ADAM
 #define PARO_TPBK_ADAM 1
+#endif
+#ifndef PARO_NT_G
+#define PARO_NT_G 0                 // ... for the reduced gradient read back in sweep 2 (dead afterwards)
+#endif
+#ifndef PARO_ADAM_REVERSE
+#define PARO_ADAM_REVERSE 0         // sweep 2 walks the range from its end (where sweep 1 wrote last)
 #endif
 #ifndef PARO_BLOCKS_PER_CU
 #define PARO_BLOCKS_PER_CU 8
@@ -110,9 +116,10 @@ __device__ __forceinline__ void st_as(V *p, V v) {
         *p = v;
 }
 
+template <bool NT = (PARO_NT_STATE != 0)>
 __device__ __forceinline__ void load8_f32(const float *p, float x[8]) {
-    f32x4 a = ld_state(reinterpret_cast<const f32x4 *>(p));
-    f32x4 b = ld_state(reinterpret_cast<const f32x4 *>(p + 4));
+    f32x4 a = ld_as<NT>(reinterpret_cast<const f32x4 *>(p));
+    f32x4 b = ld_as<NT>(reinterpret_cast<const f32x4 *>(p + 4));
     x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
     x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
 }
@@ -457,11 +464,17 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
     }
 }
 
-// Adds the per-block partials in index order (thread t takes t, t+256, ...; then
-// the fixed block tree).
+// Adds the per-block partials in a fixed order: thread t takes t, t+T, t+2T, ... (eight loads in
+// flight at a time, added in index order), then the fixed block tree.
 __global__ __launch_bounds__(TPB) void k_finalize(const double *__restrict__ partials, int n, double *out) {
     double acc = 0.0;
-    for (int k = threadIdx.x; k < n; k += TPB) acc += partials[k];
+    for (int k0 = threadIdx.x; k0 < n; k0 += 8 * TPB) {
+        double x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = (k0 + u * TPB < n) ? partials[k0 + u * TPB] : 0.0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += x[u];
+    }
     const double s = block_sum(acc);
     if (threadIdx.x == 0) *out = s;
 }
@@ -479,7 +492,8 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
     segs.s_head = s_head;
     const float sc = scale_from_norm(a, total_sumsq);
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles) {
+    TILE_LOOP(PARO_TPBK_ADAM, tile_i, ntiles) {
+        const int64_t tile = PARO_ADAM_REVERSE ? ntiles - 1 - tile_i : tile_i;
         if (MASK) segs.begin_tile(tile * TILE);
         const int rel0 = threadIdx.x * EPT;
         const int64_t e = tile * TILE + rel0;
@@ -495,7 +509,7 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
                 for (int i = 0; i < 8; ++i) decays[i] = true;
             }
             float gg[8], pp[8], mm[8], vv[8];
-            load8_f32(g + e, gg);
+            load8_f32<PARO_NT_G != 0>(g + e, gg);
             load8_f32(p + e, pp);
             load8_f32(m + e, mm);
             load8_f32(v + e, vv);
