@@ -3,20 +3,27 @@
 //
 // Everything here is bound by HBM bandwidth: per shard parameter the method
 // moves 2P bytes of bf16 contributions and 26-34 bytes of fp32 state, against
-// P adds and ~20 flops.  So the kernels are plain grid-stride sweeps built
-// around 16-byte coalesced accesses, with many independent loads in flight per
-// thread; there is no dense contraction and hence no MFMA.
+// P adds and ~20 flops.  So the kernels are plain sweeps built around 16-byte
+// coalesced accesses with many independent loads in flight per thread; there
+// is no dense contraction and hence no MFMA.
 //
 //   tile      2048 consecutive elements (256 threads x 8 elements)
-//   grid      persistent: 8 blocks per CU, block b takes tiles b, b+grid, ...
-//             so that blocks running at the same time read neighbouring
-//             addresses of every stream
+//   grid      one block per run of consecutive tiles (2 for the fold, 1 for
+//             Adam), dispatched in address order: on MI355X this beat
+//             persistent grid-stride blocks by 8-15 % for these mixed
+//             read/write streams (measured; both shapes are kept behind
+//             PARO_TPBK_*)
+//   caches    contributions are read once: streaming (non-temporal) loads;
+//             the reduced gradient is written with streaming stores, each
+//             store instruction of a wave covering 1 KB of consecutive
+//             addresses (values change lanes by shuffles first); p, m, v use
+//             the default policy (streaming hints made sweep 2 slower)
 //   fold      the P contributions of an element are added in a fixed order
 //             (never re-associated, never contracted into FMAs) so the result
 //             is bit-identical to a reduce-scatter ring run in that order
 //   norm      squares are exact in fp64; per-thread fp64 sums -> wave shuffles
 //             -> LDS -> one partial per block -> a one-block kernel adds the
-//             partials in index order.  No atomics: run-to-run identical.
+//             partials in a fixed order.  No atomics: run-to-run identical.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -44,11 +51,8 @@ namespace {
 #ifndef PARO_TPBK_ADAM
 #define PARO_TPBK_ADAM 1
 #endif
-#ifndef PARO_NT_G
-#define PARO_NT_G 0                 // ... for the reduced gradient read back in sweep 2 (dead afterwards)
-#endif
-#ifndef PARO_ADAM_REVERSE
-#define PARO_ADAM_REVERSE 0         // sweep 2 walks the range from its end (where sweep 1 wrote last)
+#ifndef PARO_G_TRANSPOSE
+#define PARO_G_TRANSPOSE 1          // sweep 1 stores the gradient with whole-wave contiguous 1 KB store instructions
 #endif
 #ifndef PARO_BLOCKS_PER_CU
 #define PARO_BLOCKS_PER_CU 8
@@ -138,6 +142,28 @@ __device__ __forceinline__ void store8_bf16(uint16_t *p, const float x[8]) {
     w.z = f32_to_bf16_rne(x[4]) | (f32_to_bf16_rne(x[5]) << 16);
     w.w = f32_to_bf16_rne(x[6]) | (f32_to_bf16_rne(x[7]) << 16);
     *reinterpret_cast<u32x4 *>(p) = w;
+}
+
+// Stores the wave's 512 results so that each of the two store instructions writes 1 KB of
+// consecutive addresses (lane l writes elements 4l..4l+3, then 256+4l..256+4l+3 of the wave's
+// span) instead of every other 16 bytes.  x[0..7] are the lane's elements 8l..8l+7; the values
+// travel between lanes by shuffles.  wave_base = address of the wave's first element.
+template <bool NT>
+__device__ __forceinline__ void store8_f32_wave_contiguous(float *wave_base, const float x[8]) {
+    const int lane = threadIdx.x & 63;
+    const int src_a = lane >> 1, src_b = 32 + (lane >> 1);
+    const bool odd = lane & 1;
+    float a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float lo_a = __shfl(x[i], src_a, 64), hi_a = __shfl(x[4 + i], src_a, 64);
+        const float lo_b = __shfl(x[i], src_b, 64), hi_b = __shfl(x[4 + i], src_b, 64);
+        a[i] = odd ? hi_a : lo_a;
+        b[i] = odd ? hi_b : lo_b;
+    }
+    f32x4 va = {a[0], a[1], a[2], a[3]}, vb = {b[0], b[1], b[2], b[3]};
+    st_as<NT>(reinterpret_cast<f32x4 *>(wave_base + 4 * lane), va);
+    st_as<NT>(reinterpret_cast<f32x4 *>(wave_base + 256 + 4 * lane), vb);
 }
 
 // Sum over the block, valid in thread 0.  Fixed shape: lanes by shuffles, then
@@ -451,7 +477,13 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
             ld.prepare(e, w);
             float X[8];
             fold8(ld, src, P, group_len, X);
-            store8_f32<PARO_NT_GSTORE != 0>(g + e, X);
+            // n is a multiple of 8 but a wave's 512-element span may be cut by the end of the range;
+            // only whole spans take the transposed path (the test is wave-uniform)
+            const int64_t wave_first = tile * TILE + (threadIdx.x & ~63) * EPT;
+            if (PARO_G_TRANSPOSE && wave_first + 64 * EPT <= n)
+                store8_f32_wave_contiguous<PARO_NT_GSTORE != 0>(g + wave_first, X);
+            else
+                store8_f32<PARO_NT_GSTORE != 0>(g + e, X);
             if (SUMSQ) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) acc += (double)X[i] * (double)X[i];
@@ -492,8 +524,7 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
     segs.s_head = s_head;
     const float sc = scale_from_norm(a, total_sumsq);
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_ADAM, tile_i, ntiles) {
-        const int64_t tile = PARO_ADAM_REVERSE ? ntiles - 1 - tile_i : tile_i;
+    TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles) {
         if (MASK) segs.begin_tile(tile * TILE);
         const int rel0 = threadIdx.x * EPT;
         const int64_t e = tile * TILE + rel0;
@@ -509,7 +540,7 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
                 for (int i = 0; i < 8; ++i) decays[i] = true;
             }
             float gg[8], pp[8], mm[8], vv[8];
-            load8_f32<PARO_NT_G != 0>(g + e, gg);
+            load8_f32(g + e, gg);
             load8_f32(p + e, pp);
             load8_f32(m + e, mm);
             load8_f32(v + e, vv);
