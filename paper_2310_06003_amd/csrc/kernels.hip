@@ -68,6 +68,7 @@ constexpr int TPB = PARO_TPB;        // threads per block
 constexpr int EPT = 8;              // elements per thread per tile
 constexpr int TILE = TPB * EPT;     // 2048 with 256 threads
 constexpr int BLOCKS_PER_CU = PARO_BLOCKS_PER_CU;
+constexpr int FINALIZE_CHUNK = 2048;  // partials per block in the first level of the final sum
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -496,19 +497,21 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
     }
 }
 
-// Adds the per-block partials in a fixed order: thread t takes t, t+T, t+2T, ... (eight loads in
-// flight at a time, added in index order), then the fixed block tree.
-__global__ __launch_bounds__(TPB) void k_finalize(const double *__restrict__ partials, int n, double *out) {
+// Adds partials in a fixed order: block b takes the slice [b*chunk, b*chunk + chunk) of the n
+// values; thread t adds its slice's elements t, t+T, t+2T, ... (eight loads in flight at a time,
+// added in index order); then the fixed block tree.  Launched as many-blocks -> one block.
+__global__ __launch_bounds__(TPB) void k_finalize(const double *__restrict__ partials, int n, int chunk, double *out) {
+    const int lo = blockIdx.x * chunk, hi = min(n, lo + chunk);
     double acc = 0.0;
-    for (int k0 = threadIdx.x; k0 < n; k0 += 8 * TPB) {
+    for (int k0 = lo + threadIdx.x; k0 < hi; k0 += 8 * TPB) {
         double x[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = (k0 + u * TPB < n) ? partials[k0 + u * TPB] : 0.0;
+        for (int u = 0; u < 8; ++u) x[u] = (k0 + u * TPB < hi) ? partials[k0 + u * TPB] : 0.0;
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += x[u];
     }
     const double s = block_sum(acc);
-    if (threadIdx.x == 0) *out = s;
+    if (threadIdx.x == 0) out[blockIdx.x] = s;
 }
 
 // Sweep 2: Adam on the stored gradient, optionally packing bf16 parameters and
@@ -654,9 +657,12 @@ int ensure_device(paro_plan_t *pl) {
     if ((rc = upload(&d.dtype, pl->dtype.data(), pl->dtype.size()))) return rc;
     if ((rc = upload(&d.no_decay, pl->no_decay.data(), pl->no_decay.size()))) return rc;
     // one partial per block of the largest sweep-1 launch (a launch covers one chunk of L elements)
+    // (a launch covers one chunk of L elements), followed by room for the second-level sums
     int64_t n_part = (pl->L + TILE - 1) / TILE;
     if (n_part < PARO_MAX_PARTIALS) n_part = PARO_MAX_PARTIALS;
-    PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), n_part * sizeof(double)));
+    d.n_partials = n_part;
+    const int64_t n_level2 = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
+    PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), (n_part + n_level2) * sizeof(double)));
     d.device = dev;
     pl->dev = d;
     return PARO_OK;
@@ -811,7 +817,16 @@ int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout,
         PARO_HIP(hipGetLastError());
     }
     if (sumsq_out) {
-        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(TPB), 0, st, pl->dev.partials, grid_for(pl, pl->L, PARO_TPBK_FOLD), sumsq_out);
+        const int n_part = grid_for(pl, pl->L, PARO_TPBK_FOLD);
+        if (n_part > 2 * FINALIZE_CHUNK) {       // two levels: slices of 2048 partials, then their sums
+            const int nb = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
+            double *level2 = pl->dev.partials + pl->dev.n_partials;
+            hipLaunchKernelGGL(k_finalize, dim3(nb), dim3(TPB), 0, st, pl->dev.partials, n_part, FINALIZE_CHUNK, level2);
+            PARO_HIP(hipGetLastError());
+            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(TPB), 0, st, level2, nb, nb, sumsq_out);
+        } else {
+            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(TPB), 0, st, pl->dev.partials, n_part, n_part, sumsq_out);
+        }
         PARO_HIP(hipGetLastError());
     }
     return PARO_OK;

@@ -15,7 +15,8 @@ struct paro_device_tables {
     int32_t *nz_tensor = nullptr;   // [n_nz]     index of that tensor in the caller's list
     uint8_t *dtype = nullptr;       // [T]
     uint8_t *no_decay = nullptr;    // [T]
-    double *partials = nullptr;     // [PARO_MAX_PARTIALS] per-block partial sums of squares
+    double *partials = nullptr;     // per-block partial sums of squares, then the second-level sums
+    int64_t n_partials = 0;         // capacity of the first level
 };
 
 struct paro_plan_s {
