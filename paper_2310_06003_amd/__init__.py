@@ -116,7 +116,7 @@ class Plan:
 
     def __del__(self):
         h, self.handle = getattr(self, "handle", None), None
-        if h:
+        if h and _lib is not None:          # at interpreter shutdown the module may already be torn down
             _lib.paro_plan_destroy(h)
 
 

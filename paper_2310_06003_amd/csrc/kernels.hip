@@ -26,6 +26,7 @@
 //             partials in a fixed order.  No atomics: run-to-run identical.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <string>
@@ -104,13 +105,24 @@ __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Pointers that were themselves loaded from memory carry no address space; these are device
+// (global) addresses by contract, so say so and get global rather than flat loads.
+template <class V>
+__device__ __forceinline__ const __attribute__((address_space(1))) V *global_ptr(uintptr_t a) {
+    return reinterpret_cast<const __attribute__((address_space(1))) V *>(a);
+}
+template <bool NT, class V>
+__device__ __forceinline__ V ld_as(const __attribute__((address_space(1))) V *p) {
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
 template <bool NT, class V>
 __device__ __forceinline__ V ld_as(const V *p) {
     if (NT) return __builtin_nontemporal_load(p);
     return *p;
 }
-template <class V>
-__device__ __forceinline__ V ld_contrib(const V *p) { return ld_as<PARO_NT_FOLD != 0>(p); }
+template <class Ptr>
+__device__ __forceinline__ auto ld_contrib(Ptr p) { return ld_as<PARO_NT_FOLD != 0>(p); }
 template <class V>
 __device__ __forceinline__ V ld_state(const V *p) { return ld_as<PARO_NT_STATE != 0>(p); }
 template <bool NT, class V>
@@ -184,16 +196,34 @@ __device__ __forceinline__ double block_sum(double v) {
     return r;
 }
 
+template <class Ld>
+__device__ __forceinline__ int64_t ld_lean_off(const Ld &ld) {
+    if constexpr (Ld::kTensor) return ld.lean_byte_off; else return 0;
+}
+
+// Compile-time loop: the body sees its index as a constant, so arrays indexed by it stay in
+// registers whatever the size of the body.
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 // Where the thread's 8 elements live: tensor (-1 = padding) and offset inside it.
 struct Where8 {
     int tens[8];
     int64_t toff[8];
     bool one_tensor;       // all 8 in one tensor (then tens[0], toff[0] describe them)
+    bool first_bf16;       // dtype of tens[0] (meaningful when tens[0] >= 0)
 };
 
 // ------------------------------------------------------------------- loaders
 // A loader hands the fold the 8 values that contribution k (in fold order)
 // holds for the thread's 8 elements.
+
+struct TileSegs;
 
 // Contributions are arrays in shard coordinates, all bf16 or all fp32.
 template <int DT>
@@ -204,6 +234,9 @@ struct ChunkLoader {
     struct Raw { u32x4 a, b; };
     int64_t e;                                   // first of the thread's 8 elements
     __device__ __forceinline__ void prepare(int64_t e0, const Where8 &) { e = e0; }
+    __device__ __forceinline__ void begin_tile(const TileSegs &, const SrcTable &, int, uintptr_t *) {}
+    __device__ __forceinline__ bool lean() const { return false; }
+    template <bool SLOW>
     __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
         if (DT == PARO_BF16) {
             r.a = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(src.p[k]) + e));
@@ -213,7 +246,8 @@ struct ChunkLoader {
             r.b = ld_contrib(q + 1);
         }
     }
-    __device__ __forceinline__ void unpack(const Raw &r, float x[8]) const {
+    template <bool SLOW>
+    __device__ __forceinline__ void unpack(const SrcTable &, int, const Raw &r, float x[8]) const {
         if (DT == PARO_BF16) {
             x[0] = bf16_lo(r.a.x); x[1] = bf16_hi(r.a.x); x[2] = bf16_lo(r.a.y); x[3] = bf16_hi(r.a.y);
             x[4] = bf16_lo(r.a.z); x[5] = bf16_hi(r.a.z); x[6] = bf16_lo(r.a.w); x[7] = bf16_hi(r.a.w);
@@ -249,14 +283,34 @@ struct TileSegs {
     int *s_head;           // [2]: index of the first segment in the table, segment count
     TensorMap tm;
     int64_t range_begin;   // flat index of shard element 0
+    const paro_tile_info *tile_tab;   // per-tile summary of this launch's range, or null
+    // set by begin_tile when the table says the whole tile lies in one tensor (then nothing is staged)
+    int single_tensor;
+    int64_t single_toff;
+    bool single_bf16;
 
     __device__ __forceinline__ void begin_tile(int64_t tile_start) {
         const int64_t f0 = range_begin + tile_start;
         const int64_t f_end = min(f0 + (int64_t)TILE, tm.total);
+        single_tensor = -1;
+        int k_known = -1;
+        if (tile_tab) {
+            const paro_tile_info info = tile_tab[tile_start / TILE];     // same address for the whole block
+            if (info.tensor >= 0) {
+                single_tensor = info.tensor;
+                single_toff = info.toff;
+                single_bf16 = info.first_seg == PARO_BF16;      // for such tiles the field holds the dtype
+                return;
+            }
+            k_known = info.first_seg;
+        }
         __syncthreads();                                   // the previous tile's readers are done
         if (threadIdx.x < 64) {
             int k_lo = tm.n_nz;
-            if (f0 < tm.total) k_lo = wave_search(tm.nz_off, tm.n_nz + 1, f0, threadIdx.x);
+            if (k_known >= 0)
+                k_lo = k_known;
+            else if (f0 < tm.total)
+                k_lo = wave_search(tm.nz_off, tm.n_nz + 1, f0, threadIdx.x);
             if (threadIdx.x == 0) {
                 s_head[0] = k_lo;
                 s_head[1] = 0;
@@ -294,6 +348,16 @@ struct TileSegs {
 };
 
 __device__ __forceinline__ void locate8(const TileSegs &segs, int rel0, Where8 &w) {
+    if (segs.single_tensor >= 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            w.tens[i] = segs.single_tensor;
+            w.toff[i] = segs.single_toff + rel0 + i;
+        }
+        w.one_tensor = true;
+        w.first_bf16 = segs.single_bf16;
+        return;
+    }
     int c = segs.find(rel0);
     const int n = segs.count();
     const int c_first = c;
@@ -313,60 +377,140 @@ __device__ __forceinline__ void locate8(const TileSegs &segs, int rel0, Where8 &
         }
     }
     w.one_tensor = c_first >= 0 && c == c_first;
+    w.first_bf16 = w.tens[0] >= 0 && segs.tm.dtype[w.tens[0]] == PARO_BF16;
 }
 
 // Contributions are per-tensor gradients: source k is a device array of T
 // pointers.  Elements map to tensors through the staged offsets.
+//
+// Fast path (the thread's 8 elements lie in one tensor): the source address has
+// whatever alignment the tensor's base and offset give it, so the thread loads the
+// 16-byte-aligned blocks that cover its 16 (bf16) or 32 (fp32) bytes - two or three
+// vector loads, the extra one shared with the neighbouring lane through the L1 - and
+// shifts the words into place.  An aligned 16-byte block that holds at least one valid
+// byte never crosses a page, so the over-read at either end of a tensor stays inside
+// mapped memory.  Slow path (a tensor boundary or padding inside the 8): element loads.
 struct TensorLoader {
     static constexpr bool kTensor = true;
     static constexpr int kBatch = 4;
-    struct Raw { float x[8]; };
+    struct Raw { u32x4 a, b, c, meta; };      // meta.x = byte offset of the first wanted byte in block a
     const uint8_t *dtype;  // [T]
-    const Where8 *w;
+    Where8 w;
+    const uintptr_t *s_ptr;   // LDS: the P base pointers of the tile's tensor, when the tile lies in one tensor
+    bool staged;
+    bool lean_;               // ... and it is bf16 and every source's first byte is 16-byte aligned
+    int64_t lean_byte_off;    // byte offset of the tile's first element inside the tensor
 
-    __device__ __forceinline__ void prepare(int64_t, const Where8 &where) { w = &where; }
+    __device__ __forceinline__ bool lean() const { return lean_; }
+
+    __device__ __forceinline__ void prepare(int64_t, const Where8 &where) { w = where; }
+
+    // When the whole tile lies in one tensor, fetch that tensor's P base pointers once per block
+    // (thread k fetches source k's) instead of once per thread and batch: the pointer look-up
+    // then costs one round trip per tile, off the critical path of the data loads.
+    __device__ __forceinline__ void begin_tile(const TileSegs &segs, const SrcTable &src, int P, uintptr_t *lds_ptr) {
+        s_ptr = lds_ptr;
+        staged = segs.single_tensor >= 0;                  // uniform over the block
+        lean_ = false;
+        if (!staged) return;
+        lean_byte_off = segs.single_toff * 2;
+        __syncthreads();                                   // the previous tile's readers are done
+        bool aligned = segs.single_bf16;
+        for (int k = threadIdx.x; k < P; k += TPB) {
+            const uintptr_t b = reinterpret_cast<uintptr_t>(static_cast<const void *const *>(src.p[k])[segs.single_tensor]);
+            lds_ptr[k] = b;
+            aligned = aligned && ((b + (uintptr_t)lean_byte_off) & 15) == 0;
+        }
+        lean_ = __syncthreads_and(aligned);                // also publishes the pointers
+    }
+
+    template <bool SLOW>
     __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
-        const void *const *ptrs = static_cast<const void *const *>(src.p[k]);
-        if (w->one_tensor) {
-            const int t = w->tens[0];
-            const bool is_bf16 = dtype[t] == PARO_BF16;
-            const char *base = static_cast<const char *>(ptrs[t]) + w->toff[0] * (is_bf16 ? 2 : 4);
-            if ((reinterpret_cast<uintptr_t>(base) & 15) == 0) {
-                if (is_bf16) {
-                    u32x4 q = ld_contrib(reinterpret_cast<const u32x4 *>(base));
-                    r.x[0] = bf16_lo(q.x); r.x[1] = bf16_hi(q.x); r.x[2] = bf16_lo(q.y); r.x[3] = bf16_hi(q.y);
-                    r.x[4] = bf16_lo(q.z); r.x[5] = bf16_hi(q.z); r.x[6] = bf16_lo(q.w); r.x[7] = bf16_hi(q.w);
-                } else {
-                    load8_f32(reinterpret_cast<const float *>(base), r.x);
+        if (SLOW && !w.one_tensor) return;
+        const int t = w.tens[0];
+        const bool is_bf16 = w.first_bf16;
+        const uintptr_t base = staged ? s_ptr[k]
+                                      : reinterpret_cast<uintptr_t>(static_cast<const void *const *>(src.p[k])[t]);
+        const uintptr_t addr = base + (uintptr_t)w.toff[0] * (is_bf16 ? 2 : 4);
+        const uintptr_t al = addr & ~(uintptr_t)15;
+        const unsigned int shift = (unsigned int)(addr & 15);
+        r.meta = u32x4{shift, 0u, 0u, 0u};
+        const bool need_b = !is_bf16 || shift != 0;
+        const bool need_c = !is_bf16 && shift != 0;
+        r.a = ld_contrib(global_ptr<u32x4>(al));
+        if (need_b) r.b = ld_contrib(global_ptr<u32x4>(al + 16));
+        if (need_c) r.c = ld_contrib(global_ptr<u32x4>(al + 32));
+    }
+
+    static __device__ __forceinline__ unsigned int sel4(unsigned int q, unsigned int w0, unsigned int w1,
+                                                        unsigned int w2, unsigned int w3) {
+        return q == 0 ? w0 : q == 1 ? w1 : q == 2 ? w2 : w3;
+    }
+
+    template <bool SLOW>
+    __device__ __forceinline__ void unpack(const SrcTable &src, int k, const Raw &r, float x[8]) const {
+        if (SLOW && !w.one_tensor) {
+            const void *const *ptrs = static_cast<const void *const *>(src.p[k]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float val = 0.0f;                           // padding contributes +0
+                const int t = w.tens[i];
+                if (t >= 0) {
+                    const void *b = ptrs[t];
+                    if (dtype[t] == PARO_BF16)
+                        val = __uint_as_float((unsigned int)static_cast<const uint16_t *>(b)[w.toff[i]] << 16);
+                    else
+                        val = static_cast<const float *>(b)[w.toff[i]];
                 }
-            } else if (is_bf16) {
-                const uint16_t *h = reinterpret_cast<const uint16_t *>(base);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) r.x[i] = __uint_as_float((unsigned int)h[i] << 16);
-            } else {
-                const float *f = reinterpret_cast<const float *>(base);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) r.x[i] = f[i];
+                x[i] = val;
             }
             return;
         }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float val = 0.0f;                               // padding contributes +0
-            const int t = w->tens[i];
-            if (t >= 0) {
-                const void *b = ptrs[t];
-                if (dtype[t] == PARO_BF16)
-                    val = __uint_as_float((unsigned int)static_cast<const uint16_t *>(b)[w->toff[i]] << 16);
-                else
-                    val = static_cast<const float *>(b)[w->toff[i]];
-            }
-            r.x[i] = val;
+        const unsigned int shift = r.meta.x;
+        const unsigned int q = shift >> 2;                  // first word that holds wanted bytes
+        if (w.first_bf16) {
+            const bool half = (shift & 2) != 0;             // the run starts in the upper half of its first word
+            static_for<0, 4>([&](auto j) {
+                const unsigned int v0 = sel4(q, word<j>(r), word<j + 1>(r), word<j + 2>(r), word<j + 3>(r));
+                const unsigned int v1 = sel4(q, word<j + 1>(r), word<j + 2>(r), word<j + 3>(r), word<j + 4>(r));
+                const unsigned int wd = half ? (v0 >> 16) | (v1 << 16) : v0;
+                x[2 * j] = bf16_lo(wd);
+                x[2 * j + 1] = bf16_hi(wd);
+            });
+        } else {
+            static_for<0, 8>([&](auto j) {
+                x[j] = __uint_as_float(sel4(q, word<j>(r), word<j + 1>(r), word<j + 2>(r), word<j + 3>(r)));
+            });
         }
     }
-    __device__ __forceinline__ void unpack(const Raw &r, float x[8]) const {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = r.x[i];
+
+    // J-th 32-bit word of the three loaded blocks, J a compile-time constant (no array, so
+    // nothing the compiler could turn into an indexed access to memory)
+    template <int J>
+    static __device__ __forceinline__ unsigned int word(const Raw &r) {
+        static_assert(J >= 0 && J < 12, "word index");
+        if constexpr (J < 4) return J == 0 ? r.a.x : J == 1 ? r.a.y : J == 2 ? r.a.z : r.a.w;
+        else if constexpr (J < 8) return J == 4 ? r.b.x : J == 5 ? r.b.y : J == 6 ? r.b.z : r.b.w;
+        else return J == 8 ? r.c.x : J == 9 ? r.c.y : J == 10 ? r.c.z : r.c.w;
+    }
+};
+
+// The tile lies in one bf16 tensor and every source is 16-byte aligned there: the same loads as
+// the chunk layout, base pointers taken from LDS.
+struct StagedBf16Loader {
+    static constexpr bool kTensor = false;
+    static constexpr int kBatch = PARO_BATCH_BF16;
+    struct Raw { u32x4 a; };
+    const uintptr_t *s_ptr;
+    int64_t byte_off;          // of the thread's first element inside the tensor
+    template <bool SLOW>
+    __device__ __forceinline__ void load(const SrcTable &, int k, Raw &r) const {
+        r.a = ld_contrib(global_ptr<u32x4>(s_ptr[k] + (uintptr_t)byte_off));
+    }
+    template <bool SLOW>
+    __device__ __forceinline__ void unpack(const SrcTable &, int, const Raw &r, float x[8]) const {
+        x[0] = bf16_lo(r.a.x); x[1] = bf16_hi(r.a.x); x[2] = bf16_lo(r.a.y); x[3] = bf16_hi(r.a.y);
+        x[4] = bf16_lo(r.a.z); x[5] = bf16_hi(r.a.z); x[6] = bf16_lo(r.a.w); x[7] = bf16_hi(r.a.w);
     }
 };
 
@@ -374,22 +518,23 @@ struct TensorLoader {
 // X[i] = contributions added in table order: runs of group_len into a partial A
 // (left to right), partials into X (left to right).  The first value of a run
 // and the first partial are copied, not added to zero (that would lose -0).
-template <class Ld>
+// SLOW (tensor layout only): some thread of the wave has a tensor boundary inside its 8
+// elements; contributions are then taken one at a time, each thread on its own path.
+template <class Ld, bool SLOW>
 __device__ __forceinline__ void fold8(const Ld &ld, const SrcTable &src, int P, int group_len, float X[8]) {
     float A[8];
     int pos = 0;
     bool first_group = true;
-    constexpr int FOLD_BATCH = Ld::kBatch;
+    constexpr int FOLD_BATCH = SLOW ? 1 : Ld::kBatch;
     for (int k0 = 0; k0 < P; k0 += FOLD_BATCH) {
         typename Ld::Raw raw[FOLD_BATCH];
-#pragma unroll
-        for (int b = 0; b < FOLD_BATCH; ++b)
-            if (k0 + b < P) ld.load(src, k0 + b, raw[b]);
-#pragma unroll
-        for (int b = 0; b < FOLD_BATCH; ++b) {
+        static_for<0, FOLD_BATCH>([&](auto b) {
+            if (k0 + b < P) ld.template load<SLOW>(src, k0 + b, raw[b]);
+        });
+        static_for<0, FOLD_BATCH>([&](auto b) {
             if (k0 + b < P) {
                 float x[8];
-                ld.unpack(raw[b], x);
+                ld.template unpack<SLOW>(src, k0 + b, raw[b], x);
                 if (pos == 0) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) A[i] = x[i];
@@ -409,7 +554,7 @@ __device__ __forceinline__ void fold8(const Ld &ld, const SrcTable &src, int P, 
                     }
                 }
             }
-        }
+        });
     }
 }
 
@@ -464,12 +609,16 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
                                                 TileSegs segs) {
     __shared__ int64_t s_off[Ld::kTensor ? TILE + 2 : 1];
     __shared__ int s_head[2];
+    __shared__ uintptr_t s_ptr[Ld::kTensor ? PARO_MAX_RANKS : 1];
     segs.s_off = s_off;
     segs.s_head = s_head;
     double acc = 0.0;
     const int64_t ntiles = (n + TILE - 1) / TILE;
     TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles) {
-        if (Ld::kTensor) segs.begin_tile(tile * TILE);
+        if (Ld::kTensor) {
+            segs.begin_tile(tile * TILE);
+            ld.begin_tile(segs, src, P, s_ptr);
+        }
         const int rel0 = threadIdx.x * EPT;
         const int64_t e = tile * TILE + rel0;
         if (e < n) {
@@ -477,7 +626,14 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
             if (Ld::kTensor) locate8(segs, rel0, w);
             ld.prepare(e, w);
             float X[8];
-            fold8(ld, src, P, group_len, X);
+            if (Ld::kTensor && ld.lean()) {
+                StagedBf16Loader lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
+                fold8<StagedBf16Loader, false>(lean, src, P, group_len, X);
+            } else if (Ld::kTensor && !__all(w.one_tensor)) {
+                fold8<Ld, true>(ld, src, P, group_len, X);
+            } else {
+                fold8<Ld, false>(ld, src, P, group_len, X);
+            }
             // n is a multiple of 8 but a wave's 512-element span may be cut by the end of the range;
             // only whole spans take the transposed path (the test is wave-uniform)
             const int64_t wave_first = tile * TILE + (threadIdx.x & ~63) * EPT;
@@ -566,12 +722,14 @@ __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P,
     constexpr bool NEED_SEGS = Ld::kTensor || MASK;
     __shared__ int64_t s_off[NEED_SEGS ? TILE + 2 : 1];
     __shared__ int s_head[2];
+    __shared__ uintptr_t s_ptr[Ld::kTensor ? PARO_MAX_RANKS : 1];
     segs.s_off = s_off;
     segs.s_head = s_head;
     const float sc = a.grad_scale;                     // no clipping on this path
     const int64_t ntiles = (n + TILE - 1) / TILE;
     TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles) {
         if (NEED_SEGS) segs.begin_tile(tile * TILE);
+        if (Ld::kTensor) ld.begin_tile(segs, src, P, s_ptr);
         const int rel0 = threadIdx.x * EPT;
         const int64_t e = tile * TILE + rel0;
         if (e < n) {
@@ -582,7 +740,14 @@ __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P,
             load8_f32(p + e, pp);
             load8_f32(m + e, mm);
             load8_f32(v + e, vv);
-            fold8(ld, src, P, group_len, X);
+            if (Ld::kTensor && ld.lean()) {
+                StagedBf16Loader lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
+                fold8<StagedBf16Loader, false>(lean, src, P, group_len, X);
+            } else if (Ld::kTensor && !__all(w.one_tensor)) {
+                fold8<Ld, true>(ld, src, P, group_len, X);
+            } else {
+                fold8<Ld, false>(ld, src, P, group_len, X);
+            }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 bool decays = true;
@@ -656,6 +821,31 @@ int ensure_device(paro_plan_t *pl) {
     if ((rc = upload(&d.nz_tensor, pl->nz_tensor.data(), pl->nz_tensor.size()))) return rc;
     if ((rc = upload(&d.dtype, pl->dtype.data(), pl->dtype.size()))) return rc;
     if ((rc = upload(&d.no_decay, pl->no_decay.data(), pl->no_decay.size()))) return rc;
+    // per-tile summaries for chunk-aligned launches over the tensor layout (16 B per 2048 elements)
+    d.tiles_per_chunk = (pl->L + TILE - 1) / TILE;
+    if (pl->T > 1 && (int64_t)pl->P * d.tiles_per_chunk <= (int64_t)4 << 20) {
+        std::vector<paro_tile_info> tab((size_t)pl->P * d.tiles_per_chunk);
+        const int64_t n_nz = (int64_t)pl->nz_tensor.size();
+        for (int c = 0; c < pl->P; ++c) {
+            for (int64_t i = 0; i < d.tiles_per_chunk; ++i) {
+                const int64_t f0 = (int64_t)c * pl->L + i * TILE;
+                const int64_t f1 = std::min(f0 + (int64_t)TILE, (int64_t)(c + 1) * pl->L);   // end of the tile
+                paro_tile_info &ti = tab[(size_t)c * d.tiles_per_chunk + i];
+                ti.toff = 0;
+                ti.tensor = -1;
+                ti.first_seg = (int32_t)n_nz;
+                if (f0 >= pl->total) continue;
+                const int64_t k = std::upper_bound(pl->nz_off.begin(), pl->nz_off.end(), f0) - pl->nz_off.begin() - 1;
+                ti.first_seg = (int32_t)k;
+                if (f1 <= pl->nz_off[k + 1]) {
+                    ti.tensor = pl->nz_tensor[k];
+                    ti.toff = f0 - pl->nz_off[k];
+                    ti.first_seg = pl->dtype[ti.tensor];          // single-tensor tiles: the field carries the dtype
+                }
+            }
+        }
+        if ((rc = upload(&d.tile_tab, tab.data(), tab.size()))) return rc;
+    }
     // one partial per block of the largest sweep-1 launch (a launch covers one chunk of L elements)
     // (a launch covers one chunk of L elements), followed by room for the second-level sums
     int64_t n_part = (pl->L + TILE - 1) / TILE;
@@ -680,7 +870,7 @@ int grid_for(const paro_plan_t *pl, int64_t n, int tpbk) {
     return (int)(ntiles < cap ? (ntiles < 1 ? 1 : ntiles) : cap);
 }
 
-TileSegs segs_for(const paro_plan_t *pl, int64_t range_begin) {
+TileSegs segs_for(const paro_plan_t *pl, int64_t range_begin, bool chunk_launch) {
     TileSegs s;
     s.s_off = nullptr;
     s.s_head = nullptr;
@@ -691,6 +881,14 @@ TileSegs segs_for(const paro_plan_t *pl, int64_t range_begin) {
     s.tm.n_nz = (int)pl->nz_tensor.size();
     s.tm.total = pl->total;
     s.range_begin = range_begin;
+    s.tile_tab = nullptr;
+    s.single_tensor = -1;
+    s.single_toff = 0;
+    s.single_bf16 = true;
+    // the per-tile table is laid out per chunk: usable when the launch starts on a chunk boundary
+    // and stays inside that chunk
+    if (pl->dev.tile_tab && chunk_launch && range_begin % pl->L == 0)
+        s.tile_tab = pl->dev.tile_tab + (range_begin / pl->L) * pl->dev.tiles_per_chunk;
     return s;
 }
 
@@ -760,10 +958,11 @@ void launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int g
                    hipStream_t st) {
     const int64_t n = pl->L;
     const int grid = grid_for(pl, n, PARO_TPBK_FOLD);
-    TileSegs segs = segs_for(pl, flat_begin);
+    TileSegs segs = segs_for(pl, flat_begin, true);
     double *partials = pl->dev.partials;
     if (layout == PARO_TENSORS) {
-        TensorLoader ld{pl->dev.dtype, nullptr};
+        TensorLoader ld;
+        ld.dtype = pl->dev.dtype;
         hipLaunchKernelGGL((k_reduce<TensorLoader, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, g,
                            partials, segs);
     } else if (pl->dtype[0] == PARO_BF16) {
@@ -782,9 +981,10 @@ void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int gr
                   const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
     const int grid = grid_for(pl, n, PARO_TPBK_FOLD);
-    TileSegs segs = segs_for(pl, flat_begin);
+    TileSegs segs = segs_for(pl, flat_begin, true);
     if (layout == PARO_TENSORS) {
-        TensorLoader ld{pl->dev.dtype, nullptr};
+        TensorLoader ld;
+        ld.dtype = pl->dev.dtype;
         hipLaunchKernelGGL((k_fused<TensorLoader, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, a,
                            p, m, v, dst, segs);
     } else if (pl->dtype[0] == PARO_BF16) {
@@ -837,7 +1037,7 @@ int do_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, c
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
     const int grid = grid_for(pl, on, PARO_TPBK_ADAM);
-    TileSegs segs = segs_for(pl, ob);
+    TileSegs segs = segs_for(pl, ob, false);
     const bool mask = pl->any_no_decay;
     if (dst && mask)
         hipLaunchKernelGGL((k_adam<true, true>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
@@ -864,6 +1064,7 @@ void paro_plan_destroy(paro_plan_t *pl) {
         (void)hipFree(pl->dev.dtype);
         (void)hipFree(pl->dev.no_decay);
         (void)hipFree(pl->dev.partials);
+        if (pl->dev.tile_tab) (void)hipFree(pl->dev.tile_tab);
     }
     delete pl;
 }

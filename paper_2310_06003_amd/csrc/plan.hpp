@@ -8,6 +8,16 @@
 
 #include "paro.h"
 
+// What a tile of a chunk-aligned launch looks like, precomputed so that the kernel does not have
+// to search: tensor >= 0: the whole tile lies inside that tensor, its first element at offset
+// toff; tensor == -1: the tile spans a tensor boundary or padding, first_seg = index of its first
+// non-empty tensor (or the table's end when the tile is all padding).
+struct paro_tile_info {
+    int64_t toff;
+    int32_t tensor;
+    int32_t first_seg;
+};
+
 struct paro_device_tables {
     int device = -1;
     int n_cu = 0;
@@ -15,6 +25,8 @@ struct paro_device_tables {
     int32_t *nz_tensor = nullptr;   // [n_nz]     index of that tensor in the caller's list
     uint8_t *dtype = nullptr;       // [T]
     uint8_t *no_decay = nullptr;    // [T]
+    paro_tile_info *tile_tab = nullptr;  // [P * tiles_per_chunk], or null when that would be too large
+    int64_t tiles_per_chunk = 0;
     double *partials = nullptr;     // per-block partial sums of squares, then the second-level sums
     int64_t n_partials = 0;         // capacity of the first level
 };
