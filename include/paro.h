@@ -173,7 +173,7 @@ int paro_pack_slot(const paro_plan_t *plan, int rank, int64_t *dst_len, int64_t 
  * PARO_EALIGN for a misaligned pointer, PARO_EINVAL for a NULL one. */
 
 /* grad_out[e] = the P contributions to element e added in the fold order of
- * e's chunk; *sumsq_out (DEVICE double, overwritten) = sum of grad_out[e]^2
+ * e's chunk; *sumsq_out (DEVICE double, overwritten; NULL = not wanted) = sum of grad_out[e]^2
  * over the rank's OWN chunk only, so that adding the ranks' values counts every
  * element of the model once. */
 int paro_reduce_shard(paro_plan_t *plan, int rank, const void *const *contrib, int layout,
@@ -203,6 +203,34 @@ int paro_pack_params(paro_plan_t *plan, int rank, const float *p, uint16_t *dst_
 int paro_step_fused(paro_plan_t *plan, int rank, const void *const *contrib, int layout,
                     const paro_adam_t *hp, float *grad_scratch, double *sumsq_scratch, float *p,
                     float *m, float *v, uint16_t *dst_base, void *stream);
+
+/* ---- the steps around the Update stage: ring hops and scheduled transfers -----
+ * One hop of a reduce-scatter ring (Sec. 3.4: each GPU passes the partial sum on
+ * to the next one after adding its own contribution), and the same operation as
+ * micro-batch gradient accumulation (Sec. 3.3: the gradients of each
+ * micro-batch are reduce-scattered inside the group and accumulated; one
+ * inter-group reduce-scatter follows the last micro-batch):
+ *   out[e] = partial_in[e] + local[e]   for 0 <= e < n, one fp32 add per element.
+ * partial_in and local are DEVICE arrays of dtype in_dtype / local_dtype
+ * (PARO_BF16 or PARO_F32), out is DEVICE fp32 and may be the same array as an
+ * fp32 partial_in or local (in-place accumulation).  All 16-byte aligned. */
+int paro_ring_hop(paro_plan_t *plan, const void *partial_in, int in_dtype, const void *local, int local_dtype,
+                  float *out, int64_t n, void *stream);
+
+/* The receive side of one step of rank `rank` in a simulated collective: for every
+ * entry of paro_schedule(plan, rank, sched, collective) with the given (phase,
+ * ring, step),
+ *   PARO_RS: bufs[rank][recv range] = bufs[recv_from][same range] + bufs[rank][recv range]   (fp32)
+ *   PARO_AG: bufs[rank][recv range] = bufs[recv_from][same range]                            (bf16)
+ * bufs: HOST array of P DEVICE pointers, rank q's padded flat buffer of
+ * paro_padded_total elements (fp32 working buffers for a reduce-scatter, bf16
+ * parameter buffers for an all-gather).  Playing every rank's steps in schedule
+ * order on one stream (inside a phase: ring 0 before ring 1) reproduces the
+ * collective: after a reduce-scatter rank r's own chunk of bufs[r] holds the sum
+ * in the fold order of paro_fold_order; after an all-gather every buffer is
+ * complete.  Returns the number of elements received (>= 0) or an error. */
+int64_t paro_collective_step(paro_plan_t *plan, int rank, int sched, int collective, int phase, int ring,
+                             int step, void *const *bufs, void *stream);
 
 /* text of the calling thread's last error ("" if none); valid until that
  * thread's next failing call */

@@ -17,7 +17,8 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 from . import plan
-from .plan import (AG, HORING, HRING, RING, RS, Layout, all_legal_strategies, chunk_of_rank,  # noqa: F401
+from .plan import (AG, HORING, HRING, RING, RS, Layout, accumulate_two_step, all_legal_strategies,  # noqa: F401
+                   chunk_of_rank,
                    default_sched, fold_order, group_of, layout, owner_of_chunk, pack_slot,
                    schedule, segments, simulate, state_range, strategy_legal, volumes)
 

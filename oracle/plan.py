@@ -282,7 +282,7 @@ def schedule(lay: Layout, sched: int, rank: int, collective: int) -> List[Msg]:
     return out
 
 
-def simulate(lay: Layout, sched: int, collective: int, bufs: List[np.ndarray]) -> None:
+def simulate(lay: Layout, sched: int, collective: int, bufs: List[np.ndarray], phases=None) -> None:
     """Literal message passing over P simulated ranks, in place.  bufs[r] is
     rank r's padded flat fp32 buffer (P*L elements).  Reduce-scatter: bufs[r]
     starts as rank r's own gradient and ends with the fully reduced chunk of
@@ -293,10 +293,12 @@ def simulate(lay: Layout, sched: int, collective: int, bufs: List[np.ndarray]) -
     for the last inter-group step of the HO-Ring reduce-scatter, whose received
     partial is added to the group's own partial of the same chunk; that add
     needs the intra-group ring of the phase to be finished, so a phase is played
-    ring 0 first, then ring 1."""
+    ring 0 first, then ring 1.  phases: play only these phases (e.g. {1} of an
+    H-Ring reduce-scatter = the intra-group reduce-scatter alone)."""
     P = lay.P
     table = [schedule(lay, sched, r, collective) for r in range(P)]
-    keys = sorted({(m.phase, m.ring, m.step) for ms in table for m in ms})
+    keys = sorted({(m.phase, m.ring, m.step) for ms in table for m in ms
+                   if phases is None or m.phase in phases})
     for key in keys:
         sel = [[m for m in table[r] if (m.phase, m.ring, m.step) == key] for r in range(P)]
         wire = {}
@@ -326,3 +328,37 @@ def volumes(lay: Layout, sched: int, rank: int, collective: int) -> Tuple[int, i
         else:
             intra += m.send_len
     return intra, inter
+
+
+def accumulate_two_step(lay: Layout, micro_batches: List[List[np.ndarray]]) -> List[np.ndarray]:
+    """Gradient accumulation with the grouped two-step reduce-scatter (Sec. 3.3,
+    PaRO-IIG / NIG): micro_batches[b][r] is rank r's padded flat fp32 gradient of
+    micro-batch b.  Every micro-batch is reduce-scattered inside the groups (the
+    intra-group ring of the H-Ring schedule); each rank adds the block it receives
+    to its persistent gradient shard (the first micro-batch is stored, the later
+    ones are added, in order); after the last micro-batch one inter-group
+    reduce-scatter runs on the accumulated blocks.  Returns, per rank, the reduced
+    chunk it owns."""
+    P, L = lay.P, lay.L
+    acc: List[np.ndarray] = []
+    for b, grads in enumerate(micro_batches):
+        bufs = [g.copy() for g in grads]
+        simulate(lay, HRING, RS, bufs, phases={1})
+        for r in range(P):
+            lo, n = state_range(lay, r, "I")
+            if b == 0:
+                acc.append(bufs[r][lo:lo + n].copy())
+            else:
+                acc[r] = acc[r] + bufs[r][lo:lo + n]          # fp32 + fp32
+    work = []
+    for r in range(P):
+        w = np.zeros(P * L, np.float32)
+        lo, n = state_range(lay, r, "I")
+        w[lo:lo + n] = acc[r]
+        work.append(w)
+    simulate(lay, HRING, RS, work, phases={2})
+    out = []
+    for r in range(P):
+        c = chunk_of_rank(r, P, lay.G)
+        out.append(work[r][c * L:(c + 1) * L].copy())
+    return out

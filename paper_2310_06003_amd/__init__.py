@@ -84,6 +84,9 @@ EXPORTS = {
     "paro_pack_params": (c_int, [c_void_p, c_int, c_void_p, c_void_p, c_void_p]),
     "paro_step_fused": (c_int, [c_void_p, c_int, POINTER(c_void_p), c_int, POINTER(paro_adam_t), c_void_p, c_void_p,
                                 c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "paro_ring_hop": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_int, c_void_p, c_int64, c_void_p]),
+    "paro_collective_step": (c_int64, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, POINTER(c_void_p),
+                                       c_void_p]),
     "paro_last_error": (c_char_p, []),
 }
 for _name, (_res, _args) in EXPORTS.items():
@@ -226,3 +229,14 @@ def paro_step_fused(plan: Plan, rank: int, contrib: Sequence[int], layout: int, 
                     sumsq_scratch: int, p: int, m: int, v: int, dst_base: int, stream: int = 0) -> None:
     _check(_lib.paro_step_fused(plan.handle, rank, _ptr_array(contrib), layout, byref(hp), grad_scratch,
                                 sumsq_scratch, p, m, v, dst_base, stream))
+
+
+def paro_ring_hop(plan: Plan, partial_in: int, in_dtype: int, local: int, local_dtype: int, out: int, n: int,
+                  stream: int = 0) -> None:
+    _check(_lib.paro_ring_hop(plan.handle, partial_in, in_dtype, local, local_dtype, out, n, stream))
+
+
+def paro_collective_step(plan: Plan, rank: int, sched: int, collective: int, phase: int, ring: int, step: int,
+                         bufs: Sequence[int], stream: int = 0) -> int:
+    return _check(_lib.paro_collective_step(plan.handle, rank, sched, collective, phase, ring, step,
+                                            _ptr_array(bufs), stream))

@@ -31,6 +31,7 @@
 #include <cstring>
 #include <string>
 #include <type_traits>
+#include <vector>
 
 #include "plan.hpp"
 
@@ -775,6 +776,46 @@ __global__ __launch_bounds__(TPB) void k_pack(const float *__restrict__ p, uint1
     }
 }
 
+// One ring hop / one accumulation: out = a + b, element by element in fp32.
+template <int DA, int DB>
+__global__ __launch_bounds__(TPB) void k_hop(const void *a, const void *b, float *out, int64_t n) {
+    const int64_t e = ((int64_t)blockIdx.x * TPB + threadIdx.x) * EPT;
+    if (e + EPT <= n) {
+        float x[8], y[8];
+        if (DA == PARO_BF16) {
+            const u32x4 q = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(a) + e));
+            x[0] = bf16_lo(q.x); x[1] = bf16_hi(q.x); x[2] = bf16_lo(q.y); x[3] = bf16_hi(q.y);
+            x[4] = bf16_lo(q.z); x[5] = bf16_hi(q.z); x[6] = bf16_lo(q.w); x[7] = bf16_hi(q.w);
+        } else {
+            load8_f32<false>(static_cast<const float *>(a) + e, x);
+        }
+        if (DB == PARO_BF16) {
+            const u32x4 q = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(b) + e));
+            y[0] = bf16_lo(q.x); y[1] = bf16_hi(q.x); y[2] = bf16_lo(q.y); y[3] = bf16_hi(q.y);
+            y[4] = bf16_lo(q.z); y[5] = bf16_hi(q.z); y[6] = bf16_lo(q.w); y[7] = bf16_hi(q.w);
+        } else {
+            load8_f32<false>(static_cast<const float *>(b) + e, y);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = x[i] + y[i];
+        store8_f32(out + e, x);
+    } else {
+        for (int64_t i = e; i < n; ++i) {                  // the last, partial group of 8
+            const float xa = DA == PARO_BF16 ? __uint_as_float((unsigned int)static_cast<const uint16_t *>(a)[i] << 16)
+                                             : static_cast<const float *>(a)[i];
+            const float xb = DB == PARO_BF16 ? __uint_as_float((unsigned int)static_cast<const uint16_t *>(b)[i] << 16)
+                                             : static_cast<const float *>(b)[i];
+            out[i] = xa + xb;
+        }
+    }
+}
+
+// Plain copy of n 16-byte units (an all-gather message landing in the parameter buffer).
+__global__ __launch_bounds__(TPB) void k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < n) dst[i] = ld_contrib(src + i);
+}
+
 }  // namespace
 
 // =========================================================================
@@ -1159,6 +1200,83 @@ int paro_step_fused(paro_plan_t *pl, int rank, const void *const *contrib, int l
         PARO_HIP(hipGetLastError());
     }
     return PARO_OK;
+}
+
+}  // extern "C"
+
+
+// ---- ring hops and scheduled transfers ----------------------------------------
+namespace {
+int launch_hop(const void *a, int da, const void *b, int db, float *out, int64_t n, hipStream_t st) {
+    if (n <= 0) return PARO_OK;
+    const int64_t groups = (n + EPT - 1) / EPT;
+    const int grid = (int)((groups + TPB - 1) / TPB);
+    if (da == PARO_BF16 && db == PARO_BF16)
+        hipLaunchKernelGGL((k_hop<PARO_BF16, PARO_BF16>), dim3(grid), dim3(TPB), 0, st, a, b, out, n);
+    else if (da == PARO_BF16)
+        hipLaunchKernelGGL((k_hop<PARO_BF16, PARO_F32>), dim3(grid), dim3(TPB), 0, st, a, b, out, n);
+    else if (db == PARO_BF16)
+        hipLaunchKernelGGL((k_hop<PARO_F32, PARO_BF16>), dim3(grid), dim3(TPB), 0, st, a, b, out, n);
+    else
+        hipLaunchKernelGGL((k_hop<PARO_F32, PARO_F32>), dim3(grid), dim3(TPB), 0, st, a, b, out, n);
+    PARO_HIP(hipGetLastError());
+    return PARO_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int paro_ring_hop(paro_plan_t *pl, const void *partial_in, int in_dtype, const void *local, int local_dtype, float *out,
+                  int64_t n, void *stream) {
+    int rc;
+    if (!pl) return fail(PARO_EINVAL, "paro_ring_hop: plan is NULL");
+    if (n < 0) return fail(PARO_EINVAL, "paro_ring_hop: n is negative");
+    if ((in_dtype != PARO_BF16 && in_dtype != PARO_F32) || (local_dtype != PARO_BF16 && local_dtype != PARO_F32))
+        return fail(PARO_EINVAL, "paro_ring_hop: bad dtype");
+    if ((rc = check_ptr(partial_in, "paro_ring_hop: partial_in"))) return rc;
+    if ((rc = check_ptr(local, "paro_ring_hop: local"))) return rc;
+    if ((rc = check_ptr(out, "paro_ring_hop: out"))) return rc;
+    if ((in_dtype == PARO_BF16 && static_cast<const void *>(out) == partial_in) ||
+        (local_dtype == PARO_BF16 && static_cast<const void *>(out) == local))
+        return fail(PARO_EINVAL, "paro_ring_hop: out may only alias an fp32 operand");
+    if ((rc = ensure_device(pl))) return rc;
+    return launch_hop(partial_in, in_dtype, local, local_dtype, out, n, static_cast<hipStream_t>(stream));
+}
+
+int64_t paro_collective_step(paro_plan_t *pl, int rank, int sched, int collective, int phase, int ring, int step,
+                             void *const *bufs, void *stream) {
+    int rc;
+    if ((rc = check_common(pl, rank, "paro_collective_step"))) return rc;
+    if (!bufs) return fail(PARO_EINVAL, "paro_collective_step: bufs is NULL");
+    for (int q = 0; q < pl->P; ++q)
+        if ((rc = check_ptr(bufs[q], "paro_collective_step: a buffer"))) return rc;
+    const int64_t count = paro_schedule(pl, rank, sched, collective, nullptr, 0);
+    if (count < 0) return count;
+    std::vector<paro_msg_t> msgs((size_t)count);
+    if (count && paro_schedule(pl, rank, sched, collective, msgs.data(), count) < 0) return PARO_EINVAL;
+    if ((rc = ensure_device(pl))) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int64_t received = 0;
+    for (const paro_msg_t &m : msgs) {
+        if (m.phase != phase || m.ring != ring || m.step != step) continue;
+        if (collective == PARO_RS) {
+            const float *from = static_cast<const float *>(bufs[m.recv_from]) + m.recv_off;
+            float *mine = static_cast<float *>(bufs[rank]) + m.recv_off;
+            if ((rc = launch_hop(from, PARO_F32, mine, PARO_F32, mine, m.recv_len, st))) return rc;
+        } else {
+            const uint16_t *from = static_cast<const uint16_t *>(bufs[m.recv_from]) + m.recv_off;
+            uint16_t *mine = static_cast<uint16_t *>(bufs[rank]) + m.recv_off;
+            const int64_t n16 = m.recv_len / 8;             // ranges are whole chunks: multiples of 8 elements
+            const int grid = (int)((n16 + TPB - 1) / TPB);
+            if (n16 > 0) {
+                hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(TPB), 0, st, reinterpret_cast<const u32x4 *>(from),
+                                   reinterpret_cast<u32x4 *>(mine), n16);
+                PARO_HIP(hipGetLastError());
+            }
+        }
+        received += m.recv_len;
+    }
+    return received;
 }
 
 }  // extern "C"

@@ -289,3 +289,60 @@ def test_layout_rejects_bad_shapes():
         orc.layout(4, 2, [])
     with pytest.raises(ValueError):
         orc.layout(4, 2, [3, -1])
+
+
+# ---- gradient accumulation with the grouped two-step reduce-scatter (Sec. 3.3) ---------
+def test_split_phases_equal_the_whole_collective():
+    P, G = 12, 4
+    lay = orc.layout(P, G, [P * 16])
+    x = _contribs(P, P * lay.L, seed=21)
+    whole = [a.copy() for a in x]
+    orc.simulate(lay, orc.HRING, orc.RS, whole)
+    split = [a.copy() for a in x]
+    orc.simulate(lay, orc.HRING, orc.RS, split, phases={1})
+    # after the intra-group phase every rank holds its group's partial of its whole block
+    for r in range(P):
+        j, i = orc.group_of(r, G)
+        lo, n = orc.state_range(lay, r, "I")
+        order = [j * G + (i + l) % G for l in range(1, G + 1)]
+        want = orc.fold([x[q][lo:lo + n] for q in order], G)
+        assert split[r][lo:lo + n].tobytes() == want.tobytes()
+    orc.simulate(lay, orc.HRING, orc.RS, split, phases={2})
+    for r in range(P):
+        c = orc.chunk_of_rank(r, P, G)
+        assert split[r][c * lay.L:(c + 1) * lay.L].tobytes() == whole[r][c * lay.L:(c + 1) * lay.L].tobytes()
+
+
+@pytest.mark.parametrize("P,G,s", [(8, 4, 3), (4, 2, 1), (6, 3, 4), (4, 4, 2), (4, 1, 2)])
+def test_accumulation_closed_form_order(P, G, s):
+    g = P // G
+    lay = orc.layout(P, G, [P * 24])
+    L = lay.L
+    mbs = [_contribs(P, P * L, seed=100 + b) for b in range(s)]
+    got = orc.accumulate_two_step(lay, mbs)
+    for r in range(P):
+        j, i = orc.group_of(r, G)
+        c = orc.chunk_of_rank(r, P, G)
+        sl = slice(c * L, (c + 1) * L)
+        # per group: intra-group ring fold of each micro-batch, micro-batches added in order;
+        # then the groups in inter-group ring order, the owner's group last
+        sums = []
+        for k in range(1, g + 1):
+            jj = (j + k) % g
+            members = [jj * G + (i + l) % G for l in range(1, G + 1)]
+            per_mb = [orc.fold([mbs[b][q][sl] for q in members], G) for b in range(s)]
+            sums.append(orc.fold(per_mb, s))
+        want = orc.fold(sums, g)
+        assert got[r].tobytes() == want.tobytes()
+
+
+def test_accumulation_small_integers_exact():
+    P, G, s = 8, 4, 5
+    lay = orc.layout(P, G, [P * 40])
+    rng = np.random.default_rng(3)
+    mbs = [[rng.integers(-8, 9, P * lay.L).astype(np.float32) for _ in range(P)] for _ in range(s)]
+    exact = np.sum([np.sum(mb, axis=0, dtype=np.int64) for mb in mbs], axis=0)
+    got = orc.accumulate_two_step(lay, mbs)
+    for r in range(P):
+        c = orc.chunk_of_rank(r, P, G)
+        assert (got[r].astype(np.int64) == exact[c * lay.L:(c + 1) * lay.L]).all()
