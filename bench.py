@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--no-clip", action="store_true", help="single-sweep path (max_norm = 0)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="elements of the shard the oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the steps around the update stage (ring hop, all-gather landing copy) at the "
+                         "same shard size and add them to the JSON line under 'extras'")
     ap.add_argument("--copy-ref", action="store_true",
                     help="only run a plain 4 GiB device copy three times (reference for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -192,6 +195,38 @@ def main():
     }
     if clip:
         out["kernels"]["sweep2_adam_pack"] = {"ms": ms2, "bytes_per_param": 30, "gbps": 30 * L / (ms2 * 1e-3) / 1e9}
+
+    if args.extras:
+        def timed(fn, reps=10):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        wire = torch.zeros(L, dtype=torch.float32, device=dev)          # partial arriving over the ring (fp32)
+        ms_hop = timed(lambda: paro.paro_ring_hop(pl, wire.data_ptr(), paro.PARO_F32, contrib[0].data_ptr(),
+                                                  paro.PARO_BF16, g.data_ptr(), L, st))
+        ms_acc = timed(lambda: paro.paro_ring_hop(pl, g.data_ptr(), paro.PARO_F32, wire.data_ptr(), paro.PARO_F32,
+                                                  g.data_ptr(), L, st))
+        # all-gather landing: one peer's packed chunk copied into this rank's parameter buffer (P = 2 toy plan
+        # whose chunk is this shard, so that one step moves exactly L bf16 elements)
+        ag = paro.paro_plan(2, 2, "NGG", [2 * L])
+        assert paro.paro_shard_len(ag) == L
+        pa = torch.zeros(2 * L, dtype=torch.bfloat16, device=dev)
+        pb = torch.ones(2 * L, dtype=torch.bfloat16, device=dev)
+        ms_ag = timed(lambda: paro.paro_collective_step(ag, 0, paro.PARO_RING, paro.PARO_AG, 1, 0, 1,
+                                                        [pa.data_ptr(), pb.data_ptr()], st))
+        out["extras"] = {
+            "ring_hop_f32_plus_bf16": {"ms": ms_hop, "bytes_per_param": 10, "gbps": 10 * L / (ms_hop * 1e-3) / 1e9},
+            "accumulate_f32_inplace": {"ms": ms_acc, "bytes_per_param": 12, "gbps": 12 * L / (ms_acc * 1e-3) / 1e9},
+            "all_gather_landing_copy_bf16": {"ms": ms_ag, "bytes_per_param": 4, "gbps": 4 * L / (ms_ag * 1e-3) / 1e9},
+        }
+        del wire, pa, pb
 
     if not args.no_cpu_baseline:
         import oracle as orc
