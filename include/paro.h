@@ -69,7 +69,7 @@ typedef struct paro_plan_s paro_plan_t; /* opaque */
 enum { PARO_OK = 0, PARO_EINVAL = -1, PARO_ESTRATEGY = -2, PARO_ERANGE = -3, PARO_ENOMEM = -4,
        PARO_EHIP = -5, PARO_EALIGN = -6 };
 enum { PARO_SCHED_DEFAULT = -1, PARO_RING = 0, PARO_HRING = 1, PARO_HORING = 2 };
-enum { PARO_BF16 = 0, PARO_F32 = 1 };          /* dtype of a tensor's gradient contributions */
+enum { PARO_BF16 = 0, PARO_F32 = 1, PARO_F16 = 2 }; /* dtype of gradient contributions / packed parameters */
 enum { PARO_CHUNK = 0, PARO_TENSORS = 1 };     /* how the contributions are laid out */
 enum { PARO_RS = 0, PARO_AG = 1 };             /* reduce-scatter, all-gather */
 enum { PARO_MAX_RANKS = 256 };                 /* largest P */
@@ -77,8 +77,10 @@ enum { PARO_MAX_RANKS = 256 };                 /* largest P */
 typedef struct {
     int32_t sched;              /* PARO_SCHED_DEFAULT: HO-Ring when 1 < G < P, else ring */
     int32_t align_elems;        /* 0 = default 8; otherwise a positive multiple of 8 */
-    const uint8_t *grad_dtype;  /* host [n_tensors] of PARO_BF16/PARO_F32, or NULL = all bf16 */
+    const uint8_t *grad_dtype;  /* host [n_tensors] of PARO_BF16/PARO_F32/PARO_F16, or NULL = all bf16 */
     const uint8_t *no_decay;    /* host [n_tensors], nonzero = exempt from weight decay, or NULL */
+    int32_t pack_dtype;         /* low-precision parameter format: PARO_BF16 (0, default) or PARO_F16 */
+    int32_t reserved_;          /* 0 */
 } paro_plan_opts_t;
 
 /* a piece of a tensor inside a range */
@@ -99,10 +101,15 @@ typedef struct {
  * gradient (1/P gives the mean).  max_norm > 0 clips by global L2 norm:
  *   coef = min(1, max_norm / (grad_scale * sqrt(total_sumsq) + 1e-6)).
  * adamw != 0: decoupled decay  p <- p*(1 - lr*wd) - step;  adamw == 0: classic
- * L2 (wd*p is added to the gradient before the moments). */
+ * L2 (wd*p is added to the gradient before the moments).
+ * skip_nonfinite != 0 (fp16 training with loss scaling; the paper says only
+ * "mixed precision"): when total_sumsq is not finite - some gradient overflowed -
+ * the update leaves p, m, v and the packed parameters untouched; the caller
+ * reads the scalar, halves its loss scale and goes on.  The un-scaling by the
+ * loss scale S is folded into grad_scale (1 / (P * S) for the mean). */
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay, grad_scale, max_norm;
-    int32_t step, adamw;
+    int32_t step, adamw, skip_nonfinite;
 } paro_adam_t;
 
 /* ---- plan (host only; needs no GPU) -------------------------------------- */
@@ -187,8 +194,8 @@ int paro_adam_shard(paro_plan_t *plan, int rank, const paro_adam_t *hp, const fl
                     const double *total_sumsq, float *p, float *m, float *v, uint16_t *dst_base,
                     void *stream);
 
-/* dst_base[slot_off + e] = bf16(p[e]), round to nearest even, over the update
- * range.  dst_base: DEVICE uint16 array of dst_len elements (paro_pack_slot),
+/* dst_base[slot_off + e] = p[e] rounded to nearest even in the plan's pack_dtype
+ * (bf16, or fp16 with overflow to infinity), over the update range.  dst_base: DEVICE uint16 array of dst_len elements (paro_pack_slot),
  * 16-byte aligned. */
 int paro_pack_params(paro_plan_t *plan, int rank, const float *p, uint16_t *dst_base, void *stream);
 
@@ -212,7 +219,7 @@ int paro_step_fused(paro_plan_t *plan, int rank, const void *const *contrib, int
  * inter-group reduce-scatter follows the last micro-batch):
  *   out[e] = partial_in[e] + local[e]   for 0 <= e < n, one fp32 add per element.
  * partial_in and local are DEVICE arrays of dtype in_dtype / local_dtype
- * (PARO_BF16 or PARO_F32), out is DEVICE fp32 and may be the same array as an
+ * (PARO_BF16, PARO_F32 or PARO_F16), out is DEVICE fp32 and may be the same array as an
  * fp32 partial_in or local (in-place accumulation).  All 16-byte aligned. */
 int paro_ring_hop(paro_plan_t *plan, const void *partial_in, int in_dtype, const void *local, int local_dtype,
                   float *out, int64_t n, void *stream);

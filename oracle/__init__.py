@@ -79,6 +79,8 @@ def fold(srcs: Sequence[np.ndarray], group_len: int, out: Optional[np.ndarray] =
     P = len(srcs)
     n = srcs[0].shape[0]
     assert P % group_len == 0 and all(s.shape[0] == n and s.dtype == srcs[0].dtype for s in srcs)
+    if srcs[0].dtype == np.float16:                 # fp16 -> fp32 is exact
+        srcs = [s.astype(np.float32) for s in srcs]
     srcs = [np.ascontiguousarray(s) for s in srcs]
     if out is None:
         out = np.empty(n, np.float32)
@@ -122,6 +124,14 @@ def bf16_rne(p: np.ndarray) -> np.ndarray:
     return out
 
 
+def f16_rne(p: np.ndarray) -> np.ndarray:
+    """fp32 -> fp16 bit patterns, IEEE round to nearest even, overflow to infinity
+    (numpy's own conversion, checked against torch's in the tests)."""
+    assert p.dtype == np.float32
+    with np.errstate(over="ignore"):
+        return p.astype(np.float16).view(np.uint16)
+
+
 def bf16_bits_to_f32(h: np.ndarray) -> np.ndarray:
     return (h.astype(np.uint32) << 16).view(np.float32)
 
@@ -154,9 +164,11 @@ def adam_shard(lay: Layout, strategy: str, rank: int, g, p, m, v, *, total_sumsq
                step: int, no_decay: Optional[Sequence[int]] = None, literal32: bool = False) -> float:
     """Clip coefficient from the global sum of squares, then Adam over the update
     range, tensor by tensor where some tensors are exempt from weight decay.
-    hp: lr, beta1, beta2, eps, weight_decay, grad_scale, max_norm, adamw.
-    Returns the clip coefficient."""
+    hp: lr, beta1, beta2, eps, weight_decay, grad_scale, max_norm, adamw,
+    skip_nonfinite.  Returns the clip coefficient (NaN for a skipped step)."""
     f = np.float32
+    if hp.get("skip_nonfinite", False) and not np.isfinite(total_sumsq):
+        return float("nan")                            # overflow somewhere: the step is skipped, nothing changes
     coef = clip_coef(total_sumsq, f(hp["grad_scale"]), f(hp.get("max_norm", 0.0)))
     sc = float(f(hp["grad_scale"])) * coef
     kw = dict(sc=sc, lr=f(hp["lr"]), beta1=f(hp["beta1"]), beta2=f(hp["beta2"]), eps=f(hp["eps"]),

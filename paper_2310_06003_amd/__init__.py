@@ -23,7 +23,7 @@ _SO = os.path.join(_HERE, "libparo.so")
 
 PARO_OK, PARO_EINVAL, PARO_ESTRATEGY, PARO_ERANGE, PARO_ENOMEM, PARO_EHIP, PARO_EALIGN = 0, -1, -2, -3, -4, -5, -6
 PARO_SCHED_DEFAULT, PARO_RING, PARO_HRING, PARO_HORING = -1, 0, 1, 2
-PARO_BF16, PARO_F32 = 0, 1
+PARO_BF16, PARO_F32, PARO_F16 = 0, 1, 2
 PARO_CHUNK, PARO_TENSORS = 0, 1
 PARO_RS, PARO_AG = 0, 1
 PARO_MAX_RANKS = 256
@@ -43,7 +43,7 @@ class ParoError(RuntimeError):
 
 class paro_plan_opts_t(Structure):
     _fields_ = [("sched", c_int32), ("align_elems", c_int32), ("grad_dtype", POINTER(c_uint8)),
-                ("no_decay", POINTER(c_uint8))]
+                ("no_decay", POINTER(c_uint8)), ("pack_dtype", c_int32), ("reserved_", c_int32)]
 
 
 class paro_seg_t(Structure):
@@ -59,7 +59,7 @@ class paro_msg_t(Structure):
 class paro_adam_t(Structure):
     _fields_ = [("lr", c_float), ("beta1", c_float), ("beta2", c_float), ("eps", c_float),
                 ("weight_decay", c_float), ("grad_scale", c_float), ("max_norm", c_float), ("step", c_int32),
-                ("adamw", c_int32)]
+                ("adamw", c_int32), ("skip_nonfinite", c_int32)]
 
 
 EXPORTS = {
@@ -125,10 +125,10 @@ class Plan:
 
 def paro_plan(P: int, G: int, strategy: str, tensor_sizes: Sequence[int], *, sched: int = PARO_SCHED_DEFAULT,
               align_elems: int = 0, grad_dtype: Optional[Sequence[int]] = None,
-              no_decay: Optional[Sequence[int]] = None) -> Plan:
+              no_decay: Optional[Sequence[int]] = None, pack_dtype: int = PARO_BF16) -> Plan:
     T = len(tensor_sizes)
     sizes = (c_int64 * max(T, 1))(*tensor_sizes)
-    opts = paro_plan_opts_t(sched, align_elems, None, None)
+    opts = paro_plan_opts_t(sched, align_elems, None, None, pack_dtype, 0)
     keep = []
     if grad_dtype is not None:
         assert len(grad_dtype) == T
@@ -203,8 +203,10 @@ def paro_pack_slot(plan: Plan, rank: int) -> Tuple[int, int, int]:
     return a.value, b.value, c.value
 
 
-def make_adam(*, lr, beta1, beta2, eps, weight_decay, grad_scale, max_norm=0.0, step=1, adamw=True) -> paro_adam_t:
-    return paro_adam_t(lr, beta1, beta2, eps, weight_decay, grad_scale, max_norm, step, 1 if adamw else 0)
+def make_adam(*, lr, beta1, beta2, eps, weight_decay, grad_scale, max_norm=0.0, step=1, adamw=True,
+              skip_nonfinite=False) -> paro_adam_t:
+    return paro_adam_t(lr, beta1, beta2, eps, weight_decay, grad_scale, max_norm, step, 1 if adamw else 0,
+                       1 if skip_nonfinite else 0)
 
 
 def _ptr_array(ptrs: Sequence[int]):

@@ -83,7 +83,7 @@ struct SrcTable {
 
 struct AdamConsts {
     float beta1, beta2, omb1, omb2, eps, step_size, sqrt_bc2, decay, wd, grad_scale, max_norm;
-    int adamw;
+    int adamw, skip_nonfinite, pack_dtype;
 };
 
 // What the kernels need to map an element of the flat buffer to its tensor.
@@ -99,6 +99,31 @@ struct TensorMap {
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ float bf16_lo(unsigned int w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(unsigned int w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// fp16 <-> fp32: the hardware conversions (exact upwards, round-to-nearest-even downwards)
+__device__ __forceinline__ float f16_bits_to_f32(unsigned int h16) {
+    return (float)__builtin_bit_cast(_Float16, (unsigned short)h16);
+}
+__device__ __forceinline__ unsigned int f32_to_f16_bits(float f) {
+    return (unsigned int)__builtin_bit_cast(unsigned short, (_Float16)f);
+}
+// the two 16-bit values of a word, as fp32, for a 2-byte gradient dtype
+template <int DT>
+__device__ __forceinline__ float cvt_lo(unsigned int w) {
+    return DT == PARO_F16 ? f16_bits_to_f32(w & 0xFFFFu) : bf16_lo(w);
+}
+template <int DT>
+__device__ __forceinline__ float cvt_hi(unsigned int w) {
+    return DT == PARO_F16 ? f16_bits_to_f32(w >> 16) : bf16_hi(w);
+}
+template <int DT>
+__device__ __forceinline__ void unpack16x8(const u32x4 &q, float x[8]) {
+    x[0] = cvt_lo<DT>(q.x); x[1] = cvt_hi<DT>(q.x); x[2] = cvt_lo<DT>(q.y); x[3] = cvt_hi<DT>(q.y);
+    x[4] = cvt_lo<DT>(q.z); x[5] = cvt_hi<DT>(q.z); x[6] = cvt_lo<DT>(q.w); x[7] = cvt_hi<DT>(q.w);
+}
+__device__ __forceinline__ float cvt16(unsigned int h16, int dt) {
+    return dt == PARO_F16 ? f16_bits_to_f32(h16) : __uint_as_float(h16 << 16);
+}
 
 __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
     unsigned int u = __float_as_uint(f);
@@ -149,12 +174,20 @@ __device__ __forceinline__ void store8_f32(float *p, const float x[8]) {
     st_as<NT>(reinterpret_cast<f32x4 *>(p + 4), b);
 }
 
-__device__ __forceinline__ void store8_bf16(uint16_t *p, const float x[8]) {
+// the low-precision copy of 8 parameters: bf16 or fp16 (block-uniform choice)
+__device__ __forceinline__ void store8_lowp(uint16_t *p, const float x[8], int pack_dtype) {
     u32x4 w;
-    w.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
-    w.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
-    w.z = f32_to_bf16_rne(x[4]) | (f32_to_bf16_rne(x[5]) << 16);
-    w.w = f32_to_bf16_rne(x[6]) | (f32_to_bf16_rne(x[7]) << 16);
+    if (pack_dtype == PARO_F16) {
+        w.x = f32_to_f16_bits(x[0]) | (f32_to_f16_bits(x[1]) << 16);
+        w.y = f32_to_f16_bits(x[2]) | (f32_to_f16_bits(x[3]) << 16);
+        w.z = f32_to_f16_bits(x[4]) | (f32_to_f16_bits(x[5]) << 16);
+        w.w = f32_to_f16_bits(x[6]) | (f32_to_f16_bits(x[7]) << 16);
+    } else {
+        w.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
+        w.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
+        w.z = f32_to_bf16_rne(x[4]) | (f32_to_bf16_rne(x[5]) << 16);
+        w.w = f32_to_bf16_rne(x[6]) | (f32_to_bf16_rne(x[7]) << 16);
+    }
     *reinterpret_cast<u32x4 *>(p) = w;
 }
 
@@ -202,6 +235,11 @@ __device__ __forceinline__ int64_t ld_lean_off(const Ld &ld) {
     if constexpr (Ld::kTensor) return ld.lean_byte_off; else return 0;
 }
 
+template <class Ld>
+__device__ __forceinline__ int ld_lean_dt(const Ld &ld) {
+    if constexpr (Ld::kTensor) return ld.lean_dt; else return PARO_BF16;
+}
+
 // Compile-time loop: the body sees its index as a constant, so arrays indexed by it stay in
 // registers whatever the size of the body.
 template <int I, int N, class F>
@@ -217,7 +255,7 @@ struct Where8 {
     int tens[8];
     int64_t toff[8];
     bool one_tensor;       // all 8 in one tensor (then tens[0], toff[0] describe them)
-    bool first_bf16;       // dtype of tens[0] (meaningful when tens[0] >= 0)
+    int first_dt;          // dtype of tens[0] (meaningful when tens[0] >= 0)
 };
 
 // ------------------------------------------------------------------- loaders
@@ -231,7 +269,7 @@ template <int DT>
 struct ChunkLoader {
     static constexpr bool kTensor = false;
     // contributions loaded before the first is consumed (16 bytes each for bf16, 32 for fp32)
-    static constexpr int kBatch = DT == PARO_BF16 ? PARO_BATCH_BF16 : 8;
+    static constexpr int kBatch = DT != PARO_F32 ? PARO_BATCH_BF16 : 8;
     struct Raw { u32x4 a, b; };
     int64_t e;                                   // first of the thread's 8 elements
     __device__ __forceinline__ void prepare(int64_t e0, const Where8 &) { e = e0; }
@@ -239,7 +277,7 @@ struct ChunkLoader {
     __device__ __forceinline__ bool lean() const { return false; }
     template <bool SLOW>
     __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
-        if (DT == PARO_BF16) {
+        if (DT != PARO_F32) {
             r.a = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(src.p[k]) + e));
         } else {
             const u32x4 *q = reinterpret_cast<const u32x4 *>(static_cast<const float *>(src.p[k]) + e);
@@ -249,9 +287,8 @@ struct ChunkLoader {
     }
     template <bool SLOW>
     __device__ __forceinline__ void unpack(const SrcTable &, int, const Raw &r, float x[8]) const {
-        if (DT == PARO_BF16) {
-            x[0] = bf16_lo(r.a.x); x[1] = bf16_hi(r.a.x); x[2] = bf16_lo(r.a.y); x[3] = bf16_hi(r.a.y);
-            x[4] = bf16_lo(r.a.z); x[5] = bf16_hi(r.a.z); x[6] = bf16_lo(r.a.w); x[7] = bf16_hi(r.a.w);
+        if (DT != PARO_F32) {
+            unpack16x8<DT>(r.a, x);
         } else {
             x[0] = __uint_as_float(r.a.x); x[1] = __uint_as_float(r.a.y);
             x[2] = __uint_as_float(r.a.z); x[3] = __uint_as_float(r.a.w);
@@ -288,7 +325,7 @@ struct TileSegs {
     // set by begin_tile when the table says the whole tile lies in one tensor (then nothing is staged)
     int single_tensor;
     int64_t single_toff;
-    bool single_bf16;
+    int single_dt;
 
     __device__ __forceinline__ void begin_tile(int64_t tile_start) {
         const int64_t f0 = range_begin + tile_start;
@@ -300,7 +337,7 @@ struct TileSegs {
             if (info.tensor >= 0) {
                 single_tensor = info.tensor;
                 single_toff = info.toff;
-                single_bf16 = info.first_seg == PARO_BF16;      // for such tiles the field holds the dtype
+                single_dt = info.first_seg;                     // for such tiles the field holds the dtype
                 return;
             }
             k_known = info.first_seg;
@@ -356,7 +393,7 @@ __device__ __forceinline__ void locate8(const TileSegs &segs, int rel0, Where8 &
             w.toff[i] = segs.single_toff + rel0 + i;
         }
         w.one_tensor = true;
-        w.first_bf16 = segs.single_bf16;
+        w.first_dt = segs.single_dt;
         return;
     }
     int c = segs.find(rel0);
@@ -378,7 +415,7 @@ __device__ __forceinline__ void locate8(const TileSegs &segs, int rel0, Where8 &
         }
     }
     w.one_tensor = c_first >= 0 && c == c_first;
-    w.first_bf16 = w.tens[0] >= 0 && segs.tm.dtype[w.tens[0]] == PARO_BF16;
+    w.first_dt = w.tens[0] >= 0 ? segs.tm.dtype[w.tens[0]] : PARO_BF16;
 }
 
 // Contributions are per-tensor gradients: source k is a device array of T
@@ -399,7 +436,8 @@ struct TensorLoader {
     Where8 w;
     const uintptr_t *s_ptr;   // LDS: the P base pointers of the tile's tensor, when the tile lies in one tensor
     bool staged;
-    bool lean_;               // ... and it is bf16 and every source's first byte is 16-byte aligned
+    bool lean_;               // ... and it is a 2-byte dtype and every source's first byte is 16-byte aligned
+    int lean_dt;
     int64_t lean_byte_off;    // byte offset of the tile's first element inside the tensor
 
     __device__ __forceinline__ bool lean() const { return lean_; }
@@ -416,7 +454,8 @@ struct TensorLoader {
         if (!staged) return;
         lean_byte_off = segs.single_toff * 2;
         __syncthreads();                                   // the previous tile's readers are done
-        bool aligned = segs.single_bf16;
+        bool aligned = segs.single_dt != PARO_F32;
+        lean_dt = segs.single_dt;
         for (int k = threadIdx.x; k < P; k += TPB) {
             const uintptr_t b = reinterpret_cast<uintptr_t>(static_cast<const void *const *>(src.p[k])[segs.single_tensor]);
             lds_ptr[k] = b;
@@ -429,7 +468,7 @@ struct TensorLoader {
     __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
         if (SLOW && !w.one_tensor) return;
         const int t = w.tens[0];
-        const bool is_bf16 = w.first_bf16;
+        const bool is_bf16 = w.first_dt != PARO_F32;        // "2-byte dtype": bf16 or fp16
         const uintptr_t base = staged ? s_ptr[k]
                                       : reinterpret_cast<uintptr_t>(static_cast<const void *const *>(src.p[k])[t]);
         const uintptr_t addr = base + (uintptr_t)w.toff[0] * (is_bf16 ? 2 : 4);
@@ -458,8 +497,9 @@ struct TensorLoader {
                 const int t = w.tens[i];
                 if (t >= 0) {
                     const void *b = ptrs[t];
-                    if (dtype[t] == PARO_BF16)
-                        val = __uint_as_float((unsigned int)static_cast<const uint16_t *>(b)[w.toff[i]] << 16);
+                    const int dt = dtype[t];
+                    if (dt != PARO_F32)
+                        val = cvt16(static_cast<const uint16_t *>(b)[w.toff[i]], dt);
                     else
                         val = static_cast<const float *>(b)[w.toff[i]];
                 }
@@ -469,14 +509,15 @@ struct TensorLoader {
         }
         const unsigned int shift = r.meta.x;
         const unsigned int q = shift >> 2;                  // first word that holds wanted bytes
-        if (w.first_bf16) {
+        if (w.first_dt != PARO_F32) {
+            const bool f16 = w.first_dt == PARO_F16;
             const bool half = (shift & 2) != 0;             // the run starts in the upper half of its first word
             static_for<0, 4>([&](auto j) {
                 const unsigned int v0 = sel4(q, word<j>(r), word<j + 1>(r), word<j + 2>(r), word<j + 3>(r));
                 const unsigned int v1 = sel4(q, word<j + 1>(r), word<j + 2>(r), word<j + 3>(r), word<j + 4>(r));
                 const unsigned int wd = half ? (v0 >> 16) | (v1 << 16) : v0;
-                x[2 * j] = bf16_lo(wd);
-                x[2 * j + 1] = bf16_hi(wd);
+                x[2 * j] = f16 ? cvt_lo<PARO_F16>(wd) : bf16_lo(wd);
+                x[2 * j + 1] = f16 ? cvt_hi<PARO_F16>(wd) : bf16_hi(wd);
             });
         } else {
             static_for<0, 8>([&](auto j) {
@@ -496,9 +537,10 @@ struct TensorLoader {
     }
 };
 
-// The tile lies in one bf16 tensor and every source is 16-byte aligned there: the same loads as
-// the chunk layout, base pointers taken from LDS.
-struct StagedBf16Loader {
+// The tile lies in one tensor of a 2-byte dtype and every source is 16-byte aligned there: the
+// same loads as the chunk layout, base pointers taken from LDS.
+template <int DT>
+struct Staged16Loader {
     static constexpr bool kTensor = false;
     static constexpr int kBatch = PARO_BATCH_BF16;
     struct Raw { u32x4 a; };
@@ -510,8 +552,7 @@ struct StagedBf16Loader {
     }
     template <bool SLOW>
     __device__ __forceinline__ void unpack(const SrcTable &, int, const Raw &r, float x[8]) const {
-        x[0] = bf16_lo(r.a.x); x[1] = bf16_hi(r.a.x); x[2] = bf16_lo(r.a.y); x[3] = bf16_hi(r.a.y);
-        x[4] = bf16_lo(r.a.z); x[5] = bf16_hi(r.a.z); x[6] = bf16_lo(r.a.w); x[7] = bf16_hi(r.a.w);
+        unpack16x8<DT>(r.a, x);
     }
 };
 
@@ -628,8 +669,13 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
             ld.prepare(e, w);
             float X[8];
             if (Ld::kTensor && ld.lean()) {
-                StagedBf16Loader lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
-                fold8<StagedBf16Loader, false>(lean, src, P, group_len, X);
+                if (ld_lean_dt(ld) == PARO_F16) {
+                    Staged16Loader<PARO_F16> lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
+                    fold8<Staged16Loader<PARO_F16>, false>(lean, src, P, group_len, X);
+                } else {
+                    Staged16Loader<PARO_BF16> lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
+                    fold8<Staged16Loader<PARO_BF16>, false>(lean, src, P, group_len, X);
+                }
             } else if (Ld::kTensor && !__all(w.one_tensor)) {
                 fold8<Ld, true>(ld, src, P, group_len, X);
             } else {
@@ -682,6 +728,8 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
     __shared__ int s_head[2];
     segs.s_off = s_off;
     segs.s_head = s_head;
+    // an overflowed (non-finite) gradient makes its sum of squares non-finite: the whole step is skipped
+    if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
     const float sc = scale_from_norm(a, total_sumsq);
     const int64_t ntiles = (n + TILE - 1) / TILE;
     TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles) {
@@ -709,7 +757,7 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
             store8_f32(p + e, pp);
             store8_f32(m + e, mm);
             store8_f32(v + e, vv);
-            if (PACK) store8_bf16(dst + e, pp);
+            if (PACK) store8_lowp(dst + e, pp, a.pack_dtype);
         }
     }
 }
@@ -742,8 +790,13 @@ __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P,
             load8_f32(m + e, mm);
             load8_f32(v + e, vv);
             if (Ld::kTensor && ld.lean()) {
-                StagedBf16Loader lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
-                fold8<StagedBf16Loader, false>(lean, src, P, group_len, X);
+                if (ld_lean_dt(ld) == PARO_F16) {
+                    Staged16Loader<PARO_F16> lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
+                    fold8<Staged16Loader<PARO_F16>, false>(lean, src, P, group_len, X);
+                } else {
+                    Staged16Loader<PARO_BF16> lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
+                    fold8<Staged16Loader<PARO_BF16>, false>(lean, src, P, group_len, X);
+                }
             } else if (Ld::kTensor && !__all(w.one_tensor)) {
                 fold8<Ld, true>(ld, src, P, group_len, X);
             } else {
@@ -758,55 +811,52 @@ __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P,
             store8_f32(p + e, pp);
             store8_f32(m + e, mm);
             store8_f32(v + e, vv);
-            store8_bf16(dst + e, pp);
+            store8_lowp(dst + e, pp, a.pack_dtype);
         }
     }
 }
 
-// bf16 pack alone.
-__global__ __launch_bounds__(TPB) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n) {
+// Low-precision pack alone.
+__global__ __launch_bounds__(TPB) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n,
+                                              int pack_dtype) {
     const int64_t ntiles = (n + TILE - 1) / TILE;
     TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles) {
         const int64_t e = tile * TILE + threadIdx.x * EPT;
         if (e < n) {
             float pp[8];
             load8_f32(p + e, pp);
-            store8_bf16(dst + e, pp);
+            store8_lowp(dst + e, pp, pack_dtype);
         }
     }
 }
 
 // One ring hop / one accumulation: out = a + b, element by element in fp32.
+template <int DT>
+__device__ __forceinline__ void hop_load8(const void *a, int64_t e, float x[8]) {
+    if (DT != PARO_F32) {
+        const u32x4 q = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(a) + e));
+        unpack16x8<DT>(q, x);
+    } else {
+        load8_f32<false>(static_cast<const float *>(a) + e, x);
+    }
+}
+template <int DT>
+__device__ __forceinline__ float hop_load1(const void *a, int64_t i) {
+    return DT != PARO_F32 ? cvt16(static_cast<const uint16_t *>(a)[i], DT) : static_cast<const float *>(a)[i];
+}
+
 template <int DA, int DB>
 __global__ __launch_bounds__(TPB) void k_hop(const void *a, const void *b, float *out, int64_t n) {
     const int64_t e = ((int64_t)blockIdx.x * TPB + threadIdx.x) * EPT;
     if (e + EPT <= n) {
         float x[8], y[8];
-        if (DA == PARO_BF16) {
-            const u32x4 q = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(a) + e));
-            x[0] = bf16_lo(q.x); x[1] = bf16_hi(q.x); x[2] = bf16_lo(q.y); x[3] = bf16_hi(q.y);
-            x[4] = bf16_lo(q.z); x[5] = bf16_hi(q.z); x[6] = bf16_lo(q.w); x[7] = bf16_hi(q.w);
-        } else {
-            load8_f32<false>(static_cast<const float *>(a) + e, x);
-        }
-        if (DB == PARO_BF16) {
-            const u32x4 q = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(b) + e));
-            y[0] = bf16_lo(q.x); y[1] = bf16_hi(q.x); y[2] = bf16_lo(q.y); y[3] = bf16_hi(q.y);
-            y[4] = bf16_lo(q.z); y[5] = bf16_hi(q.z); y[6] = bf16_lo(q.w); y[7] = bf16_hi(q.w);
-        } else {
-            load8_f32<false>(static_cast<const float *>(b) + e, y);
-        }
+        hop_load8<DA>(a, e, x);
+        hop_load8<DB>(b, e, y);
 #pragma unroll
         for (int i = 0; i < 8; ++i) x[i] = x[i] + y[i];
         store8_f32(out + e, x);
     } else {
-        for (int64_t i = e; i < n; ++i) {                  // the last, partial group of 8
-            const float xa = DA == PARO_BF16 ? __uint_as_float((unsigned int)static_cast<const uint16_t *>(a)[i] << 16)
-                                             : static_cast<const float *>(a)[i];
-            const float xb = DB == PARO_BF16 ? __uint_as_float((unsigned int)static_cast<const uint16_t *>(b)[i] << 16)
-                                             : static_cast<const float *>(b)[i];
-            out[i] = xa + xb;
-        }
+        for (int64_t i = e; i < n; ++i) out[i] = hop_load1<DA>(a, i) + hop_load1<DB>(b, i);   // last, partial group
     }
 }
 
@@ -925,7 +975,7 @@ TileSegs segs_for(const paro_plan_t *pl, int64_t range_begin, bool chunk_launch)
     s.tile_tab = nullptr;
     s.single_tensor = -1;
     s.single_toff = 0;
-    s.single_bf16 = true;
+    s.single_dt = PARO_BF16;
     // the per-tile table is laid out per chunk: usable when the launch starts on a chunk boundary
     // and stays inside that chunk
     if (pl->dev.tile_tab && chunk_launch && range_begin % pl->L == 0)
@@ -975,6 +1025,8 @@ int adam_consts(const paro_adam_t *hp, AdamConsts *a, const char *fn) {
     a->grad_scale = hp->grad_scale;
     a->max_norm = hp->max_norm;
     a->adamw = hp->adamw ? 1 : 0;
+    a->skip_nonfinite = hp->skip_nonfinite ? 1 : 0;
+    a->pack_dtype = PARO_BF16;         // the entry points overwrite it with the plan's
     return PARO_OK;
 }
 
@@ -985,7 +1037,7 @@ void src_table(const paro_plan_t *pl, int chunk, const void *const *contrib, int
     int32_t order[PARO_MAX_RANKS];
     int32_t gl = 0;
     paro::fold_order(pl, chunk, order, &gl);
-    const int64_t esize = pl->dtype[0] == PARO_BF16 ? 2 : 4;
+    const int64_t esize = pl->dtype[0] == PARO_F32 ? 4 : 2;
     for (int k = 0; k < pl->P; ++k) {
         const char *base = static_cast<const char *>(contrib[order[k]]);
         tab->p[k] = layout == PARO_CHUNK ? base + chunk_off_in_range * esize : base;
@@ -1010,6 +1062,10 @@ void launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int g
         ChunkLoader<PARO_BF16> ld{0};
         hipLaunchKernelGGL((k_reduce<ChunkLoader<PARO_BF16>, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
                            group_len, n, g, partials, segs);
+    } else if (pl->dtype[0] == PARO_F16) {
+        ChunkLoader<PARO_F16> ld{0};
+        hipLaunchKernelGGL((k_reduce<ChunkLoader<PARO_F16>, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
+                           group_len, n, g, partials, segs);
     } else {
         ChunkLoader<PARO_F32> ld{0};
         hipLaunchKernelGGL((k_reduce<ChunkLoader<PARO_F32>, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
@@ -1031,6 +1087,10 @@ void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int gr
     } else if (pl->dtype[0] == PARO_BF16) {
         ChunkLoader<PARO_BF16> ld{0};
         hipLaunchKernelGGL((k_fused<ChunkLoader<PARO_BF16>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
+                           group_len, n, a, p, m, v, dst, segs);
+    } else if (pl->dtype[0] == PARO_F16) {
+        ChunkLoader<PARO_F16> ld{0};
+        hipLaunchKernelGGL((k_fused<ChunkLoader<PARO_F16>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
                            group_len, n, a, p, m, v, dst, segs);
     } else {
         ChunkLoader<PARO_F32> ld{0};
@@ -1132,8 +1192,9 @@ int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const floa
     if ((rc = check_ptr(p, "paro_adam_shard: p"))) return rc;
     if ((rc = check_ptr(m, "paro_adam_shard: m"))) return rc;
     if ((rc = check_ptr(v, "paro_adam_shard: v"))) return rc;
-    if (a.max_norm > 0.0f && !total_sumsq)
-        return fail(PARO_EINVAL, "paro_adam_shard: clipping needs total_sumsq");
+    if ((a.max_norm > 0.0f || a.skip_nonfinite) && !total_sumsq)
+        return fail(PARO_EINVAL, "paro_adam_shard: clipping and skip_nonfinite need total_sumsq");
+    a.pack_dtype = pl->pack_dtype;
     if (dst_base && (reinterpret_cast<uintptr_t>(dst_base) & 15))
         return fail(PARO_EALIGN, "paro_adam_shard: dst_base is not 16-byte aligned");
     if ((rc = ensure_device(pl))) return rc;
@@ -1155,7 +1216,7 @@ int paro_pack_params(paro_plan_t *pl, int rank, const float *p, uint16_t *dst_ba
     int64_t dl, so, sl;
     paro_pack_slot(pl, rank, &dl, &so, &sl);
     hipLaunchKernelGGL(k_pack, dim3(grid_for(pl, sl, PARO_TPBK_ADAM)), dim3(TPB), 0, static_cast<hipStream_t>(stream), p,
-                       dst_base + so, sl);
+                       dst_base + so, sl, pl->pack_dtype);
     PARO_HIP(hipGetLastError());
     return PARO_OK;
 }
@@ -1172,11 +1233,12 @@ int paro_step_fused(paro_plan_t *pl, int rank, const void *const *contrib, int l
     if ((rc = check_ptr(m, "paro_step_fused: m"))) return rc;
     if ((rc = check_ptr(v, "paro_step_fused: v"))) return rc;
     if ((rc = check_ptr(dst_base, "paro_step_fused: dst_base"))) return rc;
-    const bool clip = a.max_norm > 0.0f;
+    a.pack_dtype = pl->pack_dtype;
+    const bool clip = a.max_norm > 0.0f || a.skip_nonfinite;       // both need the norm before the update
     if (clip) {
         if ((rc = check_ptr(grad_scratch, "paro_step_fused: grad_scratch"))) return rc;
         if (!sumsq_scratch || (reinterpret_cast<uintptr_t>(sumsq_scratch) & 7))
-            return fail(sumsq_scratch ? PARO_EALIGN : PARO_EINVAL, "paro_step_fused: clipping needs sumsq_scratch");
+            return fail(sumsq_scratch ? PARO_EALIGN : PARO_EINVAL, "paro_step_fused: clipping and skip_nonfinite need sumsq_scratch");
     }
     if ((rc = ensure_device(pl))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1211,14 +1273,12 @@ int launch_hop(const void *a, int da, const void *b, int db, float *out, int64_t
     if (n <= 0) return PARO_OK;
     const int64_t groups = (n + EPT - 1) / EPT;
     const int grid = (int)((groups + TPB - 1) / TPB);
-    if (da == PARO_BF16 && db == PARO_BF16)
-        hipLaunchKernelGGL((k_hop<PARO_BF16, PARO_BF16>), dim3(grid), dim3(TPB), 0, st, a, b, out, n);
-    else if (da == PARO_BF16)
-        hipLaunchKernelGGL((k_hop<PARO_BF16, PARO_F32>), dim3(grid), dim3(TPB), 0, st, a, b, out, n);
-    else if (db == PARO_BF16)
-        hipLaunchKernelGGL((k_hop<PARO_F32, PARO_BF16>), dim3(grid), dim3(TPB), 0, st, a, b, out, n);
-    else
-        hipLaunchKernelGGL((k_hop<PARO_F32, PARO_F32>), dim3(grid), dim3(TPB), 0, st, a, b, out, n);
+#define PARO_HOP_CASE(A, B)                                                                                   \
+    if (da == A && db == B) hipLaunchKernelGGL((k_hop<A, B>), dim3(grid), dim3(TPB), 0, st, a, b, out, n)
+    PARO_HOP_CASE(PARO_BF16, PARO_BF16); PARO_HOP_CASE(PARO_BF16, PARO_F32); PARO_HOP_CASE(PARO_BF16, PARO_F16);
+    PARO_HOP_CASE(PARO_F32, PARO_BF16);  PARO_HOP_CASE(PARO_F32, PARO_F32);  PARO_HOP_CASE(PARO_F32, PARO_F16);
+    PARO_HOP_CASE(PARO_F16, PARO_BF16);  PARO_HOP_CASE(PARO_F16, PARO_F32);  PARO_HOP_CASE(PARO_F16, PARO_F16);
+#undef PARO_HOP_CASE
     PARO_HIP(hipGetLastError());
     return PARO_OK;
 }
@@ -1231,13 +1291,13 @@ int paro_ring_hop(paro_plan_t *pl, const void *partial_in, int in_dtype, const v
     int rc;
     if (!pl) return fail(PARO_EINVAL, "paro_ring_hop: plan is NULL");
     if (n < 0) return fail(PARO_EINVAL, "paro_ring_hop: n is negative");
-    if ((in_dtype != PARO_BF16 && in_dtype != PARO_F32) || (local_dtype != PARO_BF16 && local_dtype != PARO_F32))
+    if (in_dtype < PARO_BF16 || in_dtype > PARO_F16 || local_dtype < PARO_BF16 || local_dtype > PARO_F16)
         return fail(PARO_EINVAL, "paro_ring_hop: bad dtype");
     if ((rc = check_ptr(partial_in, "paro_ring_hop: partial_in"))) return rc;
     if ((rc = check_ptr(local, "paro_ring_hop: local"))) return rc;
     if ((rc = check_ptr(out, "paro_ring_hop: out"))) return rc;
-    if ((in_dtype == PARO_BF16 && static_cast<const void *>(out) == partial_in) ||
-        (local_dtype == PARO_BF16 && static_cast<const void *>(out) == local))
+    if ((in_dtype != PARO_F32 && static_cast<const void *>(out) == partial_in) ||
+        (local_dtype != PARO_F32 && static_cast<const void *>(out) == local))
         return fail(PARO_EINVAL, "paro_ring_hop: out may only alias an fp32 operand");
     if ((rc = ensure_device(pl))) return rc;
     return launch_hop(partial_in, in_dtype, local, local_dtype, out, n, static_cast<hipStream_t>(stream));

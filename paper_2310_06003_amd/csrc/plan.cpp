@@ -142,7 +142,11 @@ int paro_plan(int P, int G, const char *strategy, const int64_t *tensor_sizes, i
                     "paro_plan: optimizer state must be sharded at least as finely as parameters and gradients");
     int sched = PARO_SCHED_DEFAULT;
     int64_t align = 8;
+    int pack_dtype = PARO_BF16;
     if (opts) {
+        pack_dtype = opts->pack_dtype;
+        if (pack_dtype != PARO_BF16 && pack_dtype != PARO_F16)
+            return fail(PARO_EINVAL, "paro_plan: pack_dtype must be PARO_BF16 or PARO_F16");
         sched = opts->sched;
         if (opts->align_elems != 0) align = opts->align_elems;
         if (sched < PARO_SCHED_DEFAULT || sched > PARO_HORING) return fail(PARO_EINVAL, "paro_plan: bad sched");
@@ -158,6 +162,7 @@ int paro_plan(int P, int G, const char *strategy, const int64_t *tensor_sizes, i
         std::memcpy(pl->letters, strategy, 3);
         pl->sched = sched == PARO_SCHED_DEFAULT ? ((G > 1 && G < P) ? PARO_HORING : PARO_RING) : sched;
         pl->align = align;
+        pl->pack_dtype = pack_dtype;
         pl->T = n_tensors;
         pl->sizes.assign(tensor_sizes, tensor_sizes + n_tensors);
         pl->off.resize(n_tensors + 1);
@@ -172,7 +177,7 @@ int paro_plan(int P, int G, const char *strategy, const int64_t *tensor_sizes, i
             pl->off[t] = acc;
             acc += tensor_sizes[t];
             if (opts && opts->grad_dtype) {
-                if (opts->grad_dtype[t] > PARO_F32) {
+                if (opts->grad_dtype[t] > PARO_F16) {
                     delete pl;
                     return fail(PARO_EINVAL, "paro_plan: bad grad_dtype");
                 }

@@ -35,6 +35,7 @@ struct paro_plan_s {
     int P = 0, G = 0, g = 0;
     char letters[4] = {0, 0, 0, 0};     // parameter, gradient, optimizer state
     int sched = PARO_RING;
+    int pack_dtype = PARO_BF16;         // dtype of the packed low-precision parameters
     int64_t align = 8;
     int64_t T = 0;
     std::vector<int64_t> sizes;         // [T]

@@ -17,7 +17,7 @@ def np_of(t: torch.Tensor) -> np.ndarray:
     t = t.detach().cpu().contiguous()
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view(np.uint16)
-    return t.numpy()
+    return t.numpy()            # float16 stays float16: numpy knows the format
 
 
 def stream() -> int:
@@ -34,7 +34,8 @@ def hp_dict(P, max_norm=0.0, adamw=True, **over):
 def hp_struct(paro, hp, step):
     return paro.make_adam(lr=hp["lr"], beta1=hp["beta1"], beta2=hp["beta2"], eps=hp["eps"],
                           weight_decay=hp["weight_decay"], grad_scale=hp["grad_scale"],
-                          max_norm=hp["max_norm"], step=step, adamw=hp["adamw"])
+                          max_norm=hp["max_norm"], step=step, adamw=hp["adamw"],
+                          skip_nonfinite=hp.get("skip_nonfinite", False))
 
 
 class PtrTable:
@@ -49,14 +50,14 @@ class PtrTable:
         return self.table.data_ptr()
 
 
-def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None, hist=None, literal=None):
+def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None, hist=None, literal=None, fmt="bf16"):
     """gpu / ref: dicts with p, m, v (fp32 numpy) and q (uint16 bf16 bits).  ref is the
     fp64 evaluation (the 1e-6 contract).  literal, when given, is the oracle's all-fp32
     evaluation in the kernel's operation order: IEEE arithmetic leaves no freedom there,
     so it must match bit for bit."""
     tol_p = check_moments_and_params(gpu["p"], gpu["m"], gpu["v"], ref["p"], ref["m"], ref["v"], p_old=p_old,
                                      m_old=m_old, g_hat=g_hat, what=what, hist=hist)
-    check_bf16_within_one_ulp(gpu["q"], ref["q"], what, ref_p=ref["p"], tol_p=tol_p)
+    check_bf16_within_one_ulp(gpu["q"], ref["q"], what, ref_p=ref["p"], tol_p=tol_p, fmt=fmt)
     if literal is not None:
         for k in ("p", "m", "v", "q"):
             a, b = gpu[k], literal[k]
@@ -67,9 +68,10 @@ def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None, hist=None,
         report.append((what, ulp_distance_f32(gpu["p"], ref["p"]), ulp_distance_f32(gpu["v"], ref["v"])))
 
 
-def oracle_update(lay, strategy, rank, g, p, m, v, *, total_sumsq, hp, step, no_decay=None, literal32=False):
+def oracle_update(lay, strategy, rank, g, p, m, v, *, total_sumsq, hp, step, no_decay=None, literal32=False,
+                  fmt="bf16"):
     """Oracle Adam + pack on copies; returns dict(p, m, v, q, coef)."""
     p, m, v = p.copy(), m.copy(), v.copy()
     coef = orc.adam_shard(lay, strategy, rank, g, p, m, v, total_sumsq=total_sumsq, hp=hp, step=step,
                           no_decay=no_decay, literal32=literal32)
-    return dict(p=p, m=m, v=v, q=orc.bf16_rne(p), coef=coef)
+    return dict(p=p, m=m, v=v, q=orc.f16_rne(p) if fmt == "f16" else orc.bf16_rne(p), coef=coef)

@@ -49,7 +49,7 @@ def ulp_distance_f32(a, b):
     return int(np.max(np.abs(ia - ib))) if a.size else 0
 
 
-def check_bf16_within_one_ulp(got_bits, ref_bits, what="", ref_p=None, tol_p=None):
+def check_bf16_within_one_ulp(got_bits, ref_bits, what="", ref_p=None, tol_p=None, fmt="bf16"):
     """bf16 bit patterns (uint16) at most one unit in the last place apart.  Where the
     parameter itself is a cancelled difference (its 1e-6 tolerance tol_p, taken on the
     terms, is large against its own size) one bf16 ulp of the tiny result means nothing:
@@ -60,8 +60,13 @@ def check_bf16_within_one_ulp(got_bits, ref_bits, what="", ref_p=None, tol_p=Non
     d = np.abs(key(got_bits) - key(ref_bits))
     bad = d > 1
     if bad.any() and ref_p is not None:
-        val = (got_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        if fmt == "f16":
+            val = np.ascontiguousarray(got_bits).view(np.float16).astype(np.float64)
+            eps = 2.0 ** -11
+        else:
+            val = (got_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+            eps = 2.0 ** -8
         ref = ref_p.astype(np.float64)
-        ok = np.abs(val - ref) <= tol_p + 2.0 ** -8 * np.maximum(np.abs(ref), np.abs(val))
+        ok = np.abs(val - ref) <= tol_p + eps * np.maximum(np.abs(ref), np.abs(val)) + (2.0 ** -25 if fmt == "f16" else 0)
         bad &= ~ok
     assert not bad.any(), f"{what} packed bf16 differs by {int(d[bad].max())} ulp"

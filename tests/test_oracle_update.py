@@ -271,3 +271,42 @@ def test_reduce_shard_equals_direct_sum_and_shards_tile_the_model(strategy):
     reps = {"G": 1, "I": P // G, "N": P}[strategy[2]]
     assert (seen == reps).all()
     assert tot == float(np.sum(flat_sum ** 2))           # every element counted once in the norm
+
+
+# ---- fp16 inputs and fp16 pack ---------------------------------------------------------
+def test_f16_pack_matches_torch_cast():
+    rng = np.random.default_rng(10)
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    for lo in [0, 1, 0x0FFF, 0x1000, 0x1001, 0x1FFF, 0x2000, 0xFFFF] + [int(x) for x in rng.integers(0, 1 << 16, 8)]:
+        x = (hi | np.uint32(lo)).view(np.float32)
+        got = orc.f16_rne(x)
+        want = torch.from_numpy(x).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+        nan = np.isnan(x)
+        assert (got[~nan] == want[~nan]).all()
+        assert ((got[nan] & 0x7C00) == 0x7C00).all() and ((got[nan] & 0x03FF) != 0).all()
+    f = lambda v: int(orc.f16_rne(np.array([v], np.float32))[0])       # noqa: E731
+    assert f(65504.0) == 0x7BFF and f(65520.0) == 0x7C00 and f(65519.9) == 0x7BFF    # overflow threshold
+    assert f(2.0 ** -24) == 0x0001 and f(2.0 ** -25) == 0x0000 and f(1.5 * 2.0 ** -25) == 0x0001
+
+
+def test_fold_of_f16_inputs_is_the_fold_of_their_exact_values():
+    rng = np.random.default_rng(12)
+    bits = [rng.integers(0, 1 << 16, 500).astype(np.uint16) for _ in range(4)]
+    for b in bits:
+        b[(b & 0x7C00) == 0x7C00] = 0x3C00
+    halves = [b.view(np.float16) for b in bits]
+    exact = [torch.from_numpy(b.view(np.int16)).view(torch.float16).float().numpy() for b in bits]
+    assert orc.fold(halves, 2).tobytes() == orc.fold(exact, 2).tobytes()
+
+
+def test_skipped_step_changes_nothing():
+    lay = orc.layout(2, 1, [64])
+    g = _rand(lay.L, 1)
+    p, m, v = _state(lay.L, 2)
+    p0, m0, v0 = p.copy(), m.copy(), v.copy()
+    hp = dict(HP, skip_nonfinite=True)
+    for tot in (float("inf"), float("nan")):
+        coef = orc.adam_shard(lay, "GGG", 0, g, p, m, v, total_sumsq=tot, hp=hp, step=1)
+        assert math.isnan(coef) and p.tobytes() == p0.tobytes() and m.tobytes() == m0.tobytes() and v.tobytes() == v0.tobytes()
+    orc.adam_shard(lay, "GGG", 0, g, p, m, v, total_sumsq=1.0, hp=hp, step=1)
+    assert p.tobytes() != p0.tobytes()

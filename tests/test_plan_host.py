@@ -49,7 +49,7 @@ def test_plan_errors(paro):
             paro.paro_plan(*args)
         assert ei.value.code == E, args
         assert paro.paro_last_error()
-    for kw in [dict(sched=7), dict(align_elems=4), dict(align_elems=12), dict(grad_dtype=[2])]:
+    for kw in [dict(sched=7), dict(align_elems=4), dict(align_elems=12), dict(grad_dtype=[3]), dict(pack_dtype=1), dict(pack_dtype=5)]:
         with pytest.raises(paro.ParoError) as ei:
             paro.paro_plan(4, 2, "GGG", [8], **kw)
         assert ei.value.code == E, kw

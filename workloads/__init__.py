@@ -17,6 +17,8 @@ import torch
 
 BF16 = 0  # gradient dtype codes, same numbering on both sides of the boundary
 F32 = 1
+F16 = 2
+TORCH_DTYPE = {BF16: torch.bfloat16, F32: torch.float32, F16: torch.float16}
 
 ADAM_DEFAULT = dict(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
 
@@ -121,7 +123,7 @@ def draw(n: int, seed: int, *, dist: str = "normal", scale: float = 1e-3,
          dtype: int = BF16, device="cpu", piece: int = 1 << 27) -> torch.Tensor:
     """n seeded values, scale * N(0,1) or scale * Student-t(df=3), as bf16 or
     fp32.  Drawn in pieces so the fp32 temporaries stay small on the device."""
-    tdt = torch.bfloat16 if dtype == BF16 else torch.float32
+    tdt = TORCH_DTYPE[dtype]
     out = torch.empty(n, dtype=tdt, device=device)
     gen = _generator(device, seed)
     for lo in range(0, n, piece):
@@ -144,7 +146,7 @@ def draw_int(n: int, seed: int, *, lo: int = -8, hi: int = 8, dtype: int = BF16,
     """Small-integer-valued gradients (exactly representable in bf16)."""
     gen = _generator(device, seed)
     z = torch.randint(lo, hi + 1, (n,), generator=gen, device=device, dtype=torch.int32)
-    return z.to(torch.bfloat16 if dtype == BF16 else torch.float32)
+    return z.to(TORCH_DTYPE[dtype])
 
 
 def chunk_contribs(P: int, n: int, base_seed: int, step: int = 0, *, dist="normal",
