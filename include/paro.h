@@ -239,6 +239,39 @@ int paro_ring_hop(paro_plan_t *plan, const void *partial_in, int in_dtype, const
 int64_t paro_collective_step(paro_plan_t *plan, int rank, int sched, int collective, int phase, int ring,
                              int step, void *const *bufs, void *stream);
 
+/* ---- cost model (host only): the paper's Tables 1-3 and Eq. 1 as a function ------
+ * Memory per GPU in bytes (Table 2: 2*Psi/d, 2*Psi'/d, K*Psi'/d with d = 1, M, N for
+ * N / I / G) and communication volume in ELEMENTS, summed over all GPUs, for one
+ * mini-batch of s micro-batches (Table 3), split into intra-group and inter-group
+ * traffic.  sched picks the global collective: PARO_RING gives the flat-ring rows
+ * (ZeRO-1/2/3), PARO_HORING (or PARO_HRING, same volumes) the HO-Ring rows (PaRO-IGG
+ * backward reduce-scatter, PaRO-NIG update all-gather); PARO_SCHED_DEFAULT = HO-Ring when
+ * 1 < M < N.  Rows the paper prints (NNG, NGG, GGG, III, IGG, IIG, NIG) are reproduced as
+ * printed, including the all-reduce of ZeRO-1 and MiCS; the other strategies follow the
+ * same rules (Sec. 3.1.1) and are marked derived = 1.  recommended[c] is Table 1's mark for
+ * column c (0: Psi' = Psi, 1: Psi' >= Psi/6, 2: Psi' < Psi/6, 3: PEFT). */
+typedef struct {
+    double mem_param, mem_grad, mem_os;
+    double fwd_ag_intra, fwd_ag_inter;      /* forward all-gather of parameters */
+    double bwd_ag_intra, bwd_ag_inter;      /* backward all-gather of parameters */
+    double bwd_rs_intra, bwd_rs_inter;      /* backward reduce-scatter of gradients */
+    double upd_g_intra, upd_g_inter;        /* update stage: reduce-scatter / all-reduce of gradients */
+    double upd_ag_intra, upd_ag_inter;      /* update stage: all-gather of parameters */
+    int32_t recommended[4];
+    int32_t derived;
+} paro_cost_t;
+
+/* N GPUs in groups of M (M divides N), s >= 1 micro-batches, K bytes of optimizer state
+ * per trainable parameter (12 for mixed-precision Adam, Sec. 3.1.2).  PARO_ESTRATEGY for a
+ * strategy outside Table 1, PARO_EINVAL for bad numbers. */
+int paro_cost(const char *strategy, double psi, double psi_trainable, int N, int M, int s, int K, int sched,
+              paro_cost_t *out);
+
+/* Eq. 1: elements a GPU no longer sends when the global reduce-scatter of every
+ * micro-batch is replaced by an intra-group one per micro-batch plus one inter-group one
+ * per mini-batch: Psi * (s - 1) * (g - 1) / N. */
+double paro_two_step_saving(double psi, int N, int M, int s);
+
 /* text of the calling thread's last error ("" if none); valid until that
  * thread's next failing call */
 const char *paro_last_error(void);

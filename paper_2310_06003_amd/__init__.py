@@ -9,7 +9,8 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import POINTER, Structure, byref, c_char, c_char_p, c_float, c_int, c_int32, c_int64, c_uint8, c_void_p
+from ctypes import (POINTER, Structure, byref, c_char, c_char_p, c_double, c_float, c_int, c_int32, c_int64, c_uint8,
+                    c_void_p)
 from typing import List, Optional, Sequence, Tuple
 
 # The caller's device buffers and streams come from PyTorch, which ships its own copy of the HIP
@@ -62,6 +63,13 @@ class paro_adam_t(Structure):
                 ("adamw", c_int32), ("skip_nonfinite", c_int32)]
 
 
+class paro_cost_t(Structure):
+    _fields_ = [(k, c_double) for k in ("mem_param", "mem_grad", "mem_os", "fwd_ag_intra", "fwd_ag_inter",
+                                        "bwd_ag_intra", "bwd_ag_inter", "bwd_rs_intra", "bwd_rs_inter",
+                                        "upd_g_intra", "upd_g_inter", "upd_ag_intra", "upd_ag_inter")] + \
+               [("recommended", c_int32 * 4), ("derived", c_int32)]
+
+
 EXPORTS = {
     "paro_strategy_legal": (c_int, [c_char_p]),
     "paro_plan": (c_int, [c_int, c_int, c_char_p, POINTER(c_int64), c_int64, POINTER(paro_plan_opts_t),
@@ -87,6 +95,8 @@ EXPORTS = {
     "paro_ring_hop": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_int, c_void_p, c_int64, c_void_p]),
     "paro_collective_step": (c_int64, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, POINTER(c_void_p),
                                        c_void_p]),
+    "paro_cost": (c_int, [c_char_p, c_double, c_double, c_int, c_int, c_int, c_int, c_int, POINTER(paro_cost_t)]),
+    "paro_two_step_saving": (c_double, [c_double, c_int, c_int, c_int]),
     "paro_last_error": (c_char_p, []),
 }
 for _name, (_res, _args) in EXPORTS.items():
@@ -242,3 +252,17 @@ def paro_collective_step(plan: Plan, rank: int, sched: int, collective: int, pha
                          bufs: Sequence[int], stream: int = 0) -> int:
     return _check(_lib.paro_collective_step(plan.handle, rank, sched, collective, phase, ring, step,
                                             _ptr_array(bufs), stream))
+
+
+def paro_cost(strategy: str, psi: float, psi_trainable: float, N: int, M: int, s: int, K: int = 12,
+              sched: int = PARO_SCHED_DEFAULT) -> dict:
+    out = paro_cost_t()
+    _check(_lib.paro_cost(strategy.encode(), psi, psi_trainable, N, M, s, K, sched, byref(out)))
+    d = {k: getattr(out, k) for k, _ in paro_cost_t._fields_ if k not in ("recommended", "derived")}
+    d["recommended"] = list(out.recommended)
+    d["derived"] = bool(out.derived)
+    return d
+
+
+def paro_two_step_saving(psi: float, N: int, M: int, s: int) -> float:
+    return float(_lib.paro_two_step_saving(psi, N, M, s))

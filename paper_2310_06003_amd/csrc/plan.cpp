@@ -316,6 +316,77 @@ int64_t paro_schedule(const paro_plan_t *pl, int rank, int sched, int collective
     return (int64_t)msgs.size();
 }
 
+int paro_cost(const char *strategy, double psi, double psit, int N, int M, int s, int K, int sched, paro_cost_t *out) {
+    if (!out) return fail(PARO_EINVAL, "paro_cost: out is NULL");
+    if (!paro_strategy_legal(strategy)) return fail(PARO_ESTRATEGY, "paro_cost: strategy is not one of Table 1's");
+    if (N < 1 || M < 1 || N % M != 0 || s < 1 || K < 0 || !(psi > 0) || !(psit >= 0) || psit > psi)
+        return fail(PARO_EINVAL, "paro_cost: need N >= 1, M | N, s >= 1, K >= 0, 0 <= Psi' <= Psi");
+    if (sched < PARO_SCHED_DEFAULT || sched > PARO_HORING) return fail(PARO_EINVAL, "paro_cost: bad sched");
+    const bool ring = sched == PARO_RING || (sched == PARO_SCHED_DEFAULT && !(M > 1 && M < N));
+    const double g = (double)N / M, n = N, m = M, sd = s;
+    std::memset(out, 0, sizeof *out);
+    auto div = [&](char c) { return c == 'N' ? 1.0 : c == 'I' ? m : n; };
+    out->mem_param = 2.0 * psi / div(strategy[0]);
+    out->mem_grad = 2.0 * psit / div(strategy[1]);
+    out->mem_os = (double)K * psit / div(strategy[2]);
+
+    struct Vol { double intra, inter; };
+    // one collective over all N GPUs on x elements (messages of x/N)
+    auto global = [&](double x) -> Vol {
+        if (ring) {
+            const double links_inter = g > 1 ? g : 0;          // the flat ring crosses a group border g times
+            return {(n - links_inter) * x / n * (n - 1), links_inter * x / n * (n - 1)};
+        }
+        return {n * x / m * (m - 1), n * x / n * (g - 1)};     // HO-Ring / H-Ring
+    };
+    auto intra_group = [&](double x) -> Vol { return {n * x / m * (m - 1), 0.0}; };
+    auto inter_group = [&](double x) -> Vol { return {0.0, n * x / n * (g - 1)}; };
+    auto add = [](double &a, double &b, Vol v, double times) { a += v.intra * times; b += v.inter * times; };
+
+    const char sp = strategy[0], sg = strategy[1], so = strategy[2];
+    // parameters are gathered before use in forward and in backward, every micro-batch (Sec. 3.1.1)
+    if (sp == 'I') {
+        add(out->fwd_ag_intra, out->fwd_ag_inter, intra_group(psi), sd);
+        add(out->bwd_ag_intra, out->bwd_ag_inter, intra_group(psi), sd);
+    } else if (sp == 'G') {
+        add(out->fwd_ag_intra, out->fwd_ag_inter, global(psi), sd);
+        add(out->bwd_ag_intra, out->bwd_ag_inter, global(psi), sd);
+    }
+    // sharded gradients are reduce-scattered every micro-batch
+    if (sg == 'I') add(out->bwd_rs_intra, out->bwd_rs_inter, intra_group(psit), sd);
+    if (sg == 'G') add(out->bwd_rs_intra, out->bwd_rs_inter, global(psit), sd);
+    // update stage, once per mini-batch: bring the gradients to the optimizer state's sharding ...
+    if (sg == 'N') {                                   // unsharded gradients: all-reduce (ZeRO-1 row, bold)
+        add(out->upd_g_intra, out->upd_g_inter, global(psit), 2.0);
+    } else if (sg == 'I' && so == 'G') {               // PaRO-IIG / NIG rows
+        add(out->upd_g_intra, out->upd_g_inter, inter_group(psit), 1.0);
+    } else if (sg == 'I' && so == 'I') {               // MiCS row: all-reduce of the group shard across groups
+        out->upd_g_inter += 2.0 * g * psit / m * (g - 1);
+        out->upd_g_intra += 2.0 * (n - g) * psit / m * (g - 1);
+    }
+    // ... and the updated parameters back to the parameters' sharding
+    if (sp == 'N' && so == 'G') add(out->upd_ag_intra, out->upd_ag_inter, global(psi), 1.0);
+    if (sp == 'I' && so == 'G') add(out->upd_ag_intra, out->upd_ag_inter, inter_group(psi), 1.0);
+    if (sp == 'N' && so == 'I') add(out->upd_ag_intra, out->upd_ag_inter, intra_group(psi), 1.0);
+
+    static const struct { const char *s; int rec[4]; int printed; } table1[] = {
+        {"NNN", {1, 1, 1, 1}, 0}, {"NNI", {1, 1, 1, 1}, 0}, {"NNG", {1, 1, 1, 0}, 1}, {"NII", {1, 1, 1, 0}, 0},
+        {"NIG", {1, 1, 1, 0}, 1}, {"NGG", {1, 1, 1, 0}, 1}, {"INI", {0, 0, 0, 1}, 0}, {"ING", {0, 1, 1, 0}, 0},
+        {"III", {0, 0, 1, 0}, 1}, {"IIG", {1, 1, 0, 0}, 1}, {"IGG", {1, 1, 1, 0}, 1}, {"GNG", {0, 1, 1, 1}, 0},
+        {"GIG", {0, 1, 1, 0}, 0}, {"GGG", {1, 1, 1, 0}, 1}};
+    for (const auto &row : table1)
+        if (std::strcmp(row.s, strategy) == 0) {
+            for (int c = 0; c < 4; ++c) out->recommended[c] = row.rec[c];
+            out->derived = row.printed ? 0 : 1;
+        }
+    return PARO_OK;
+}
+
+double paro_two_step_saving(double psi, int N, int M, int s) {
+    if (N < 1 || M < 1 || N % M != 0 || s < 1) return 0.0;
+    return psi * (s - 1) * ((double)N / M - 1) / N;
+}
+
 int paro_pack_slot(const paro_plan_t *pl, int rank, int64_t *dst_len, int64_t *slot_off, int64_t *slot_len) {
     if (!rank_ok(pl, rank)) return fail(PARO_ERANGE, "paro_pack_slot: rank out of range");
     if (!dst_len || !slot_off || !slot_len) return fail(PARO_EINVAL, "paro_pack_slot: NULL output");

@@ -1,0 +1,86 @@
+"""The cost model of libparo (host only) against the paper's Tables 1-3 and Eq. 1."""
+import itertools
+import os
+
+import pytest
+
+import oracle as orc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+SETTINGS = [dict(N=64, M=8, s=8, Psi=7e9),          # the setting of Fig. 5
+            dict(N=16, M=8, s=1, Psi=6738415616.0), dict(N=128, M=8, s=10, Psi=65285660672.0),
+            dict(N=9, M=3, s=4, Psi=9e6), dict(N=8, M=8, s=2, Psi=1e6), dict(N=8, M=1, s=3, Psi=1e6)]
+SCHED = {"ring": 0, "horing": 2}
+
+
+def _table3():
+    rows = []
+    for ln in open(os.path.join(GOLD, "table3_volumes.txt")):
+        if ln.strip() and not ln.startswith("#"):
+            cells = [c.strip() for c in ln.split("|")]
+            rows.append((cells[0], cells[1], cells[2], [tuple(x.strip() for x in c.split(";")) for c in cells[3:]]))
+    return rows
+
+
+@pytest.mark.parametrize("setting", SETTINGS)
+def test_table3_rows(paro, setting):
+    N, M, s, Psi = setting["N"], setting["M"], setting["s"], setting["Psi"]
+    env = dict(N=N, M=M, g=N / M, s=s, Psi=Psi)
+    for name, strat, sched, cells in _table3():
+        if N // M == 1 and sched == "ring":
+            continue        # with a single group the printed flat-ring split (g inter-group links) does not apply
+        c = paro.paro_cost(strat, Psi, Psi, N, M, s, 12, SCHED[sched])
+        assert not c["derived"], name
+        for key, (intra, inter) in zip(("fwd_ag", "bwd_ag", "bwd_rs", "upd_g", "upd_ag"), cells):
+            assert c[key + "_intra"] == pytest.approx(eval(intra, {}, env), rel=1e-12), (name, key)
+            assert c[key + "_inter"] == pytest.approx(eval(inter, {}, env), rel=1e-12), (name, key)
+
+
+def test_table2_memory_and_table1_marks(paro):
+    N, M, Psi, K = 64, 8, 7e9, 12
+    div = {"1": 1, "M": M, "N": N}
+    for ln in open(os.path.join(GOLD, "table2_memory.txt")):
+        if ln.strip() and not ln.startswith("#"):
+            name, strat, dp, dg, dos = ln.split()
+            c = paro.paro_cost(strat, Psi, Psi, N, M, 8, K)
+            assert (c["mem_param"], c["mem_grad"], c["mem_os"]) == (2 * Psi / div[dp], 2 * Psi / div[dg], K * Psi / div[dos])
+    for ln in open(os.path.join(GOLD, "table1_strategies.txt")):
+        if ln.strip() and not ln.startswith("#"):
+            strat, *marks = ln.split()
+            assert paro.paro_cost(strat, Psi, Psi, N, M, 8)["recommended"] == [int(x == "Y") for x in marks]
+    # partial training: gradients and optimizer state shrink with the trainable share, parameters do not
+    c = paro.paro_cost("IIG", Psi, Psi / 10, N, M, 8, K)
+    assert (c["mem_param"], c["mem_grad"], c["mem_os"]) == (2 * Psi / M, 2 * Psi / 10 / M, K * Psi / 10 / N)
+
+
+def test_eq1_and_orders(paro):
+    for N, M, s, Psi in [(64, 8, 8, 7e9), (16, 8, 10, 1e9), (8, 8, 4, 1e6), (8, 2, 1, 1e6)]:
+        g = N // M
+        assert paro.paro_two_step_saving(Psi, N, M, s) == pytest.approx(Psi * (s - 1) * (g - 1) / N)
+        # the same number from the cost rows: a global ring reduce-scatter per micro-batch (ZeRO-2) against
+        # the intra-group one per micro-batch plus one inter-group one (PaRO-NIG), per GPU
+        z2 = paro.paro_cost("NGG", Psi, Psi, N, M, s, 12, 0)
+        nig = paro.paro_cost("NIG", Psi, Psi, N, M, s, 12, 2)
+        per_gpu = lambda c: (c["bwd_rs_intra"] + c["bwd_rs_inter"] + c["upd_g_intra"] + c["upd_g_inter"]) / N   # noqa: E731
+        assert per_gpu(z2) - per_gpu(nig) == pytest.approx(paro.paro_two_step_saving(Psi, N, M, s), rel=1e-9, abs=1e-3)
+    # Sec. 3.1: memory G < I < N, and every strategy is either printed in Table 3 or marked derived
+    N, M, Psi = 64, 8, 7e9
+    printed = {r[1] for r in _table3()}
+    for strat in orc.all_legal_strategies():
+        c = paro.paro_cost(strat, Psi, Psi, N, M, 8)
+        assert c["derived"] == (strat not in printed)
+    mem = lambda s_: sum(paro.paro_cost(s_, Psi, Psi, N, M, 8)[k] for k in ("mem_param", "mem_grad", "mem_os"))   # noqa: E731
+    assert mem("GGG") < mem("IGG") < mem("IIG") < mem("III") < mem("NII") < mem("NNI") < mem("NNN")
+    # inter-group volume: PaRO-IIG is the lowest of the sharded-parameter strategies (Fig. 5's reading)
+    inter = lambda s_, sc: sum(v for k, v in paro.paro_cost(s_, Psi, Psi, N, M, 8, 12, sc).items() if k.endswith("_inter"))   # noqa: E731
+    assert inter("IIG", 2) < inter("IGG", 2) < inter("GGG", 0)
+
+
+def test_cost_errors(paro):
+    with pytest.raises(paro.ParoError) as e:
+        paro.paro_cost("GGN", 1e6, 1e6, 8, 4, 1)
+    assert e.value.code == paro.PARO_ESTRATEGY
+    for args in [(1e6, 1e6, 8, 3, 1), (1e6, 1e6, 0, 1, 1), (1e6, 2e6, 8, 4, 1), (1e6, 1e6, 8, 4, 0), (0.0, 0.0, 8, 4, 1)]:
+        with pytest.raises(paro.ParoError) as e:
+            paro.paro_cost("GGG", *args)
+        assert e.value.code == paro.PARO_EINVAL
