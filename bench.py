@@ -38,7 +38,9 @@ def parse():
     ap.add_argument("--workload", default="llama7b_share",
                     choices=["llama7b_share", "llama65b_share", "tiny_share"])
     ap.add_argument("--no-clip", action="store_true", help="single-sweep path (max_norm = 0)")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 25, help="elements of the shard the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=0,
+                    help="elements of the shard the oracle is timed on with all threads (0 = the whole shard, "
+                         "about 10 s of CPU work in all at the default workload)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", action="store_true",
                     help="also time the steps around the update stage (ring hop, all-gather landing copy) at the "
@@ -230,7 +232,7 @@ def main():
 
     if not args.no_cpu_baseline:
         import oracle as orc
-        n = min(args.cpu_sample, L)
+        n = min(args.cpu_sample, L) if args.cpu_sample > 0 else L
         order, gl = orc.fold_order(P, G, orc.default_sched(P, G), orc.chunk_of_rank(rank, P, G))
         host = [contrib[q][:n].cpu().view(torch.int16).numpy().view(np.uint16) for q in order]
         p0, m0, v0 = wl.master_state(n, 7)
@@ -251,12 +253,13 @@ def main():
         nthreads = orc.threads()
         oracle_step(nthreads, min(n, 1 << 20))                       # page in
         rate_all = max(oracle_step(nthreads, n) for _ in range(2))
-        n1 = min(n, 1 << 23)
+        n1 = min(n, 1 << 27)
         rate_one = oracle_step(1, n1)
         orc.set_threads(nthreads)
         out["cpu_baseline"] = {"value": rate_all, "unit": "params/s", "cores": nthreads, "kind": "oracle",
-                               "sample": f"first {n} shard elements of the same buffers, all {P} contributions, "
-                                         f"one fused step (fold + sum of squares + clip + Adam fp64 + pack)",
+                               "sample": (f"{'the whole shard' if n == L else 'first ' + str(n) + ' shard elements'} of the "
+                                          f"same buffers ({n} elements), all {P} contributions, one fused step (fold + "
+                                          f"sum of squares + clip + Adam fp64 + pack), best of 2"),
                                "single_thread": {"value": rate_one, "cores": 1, "sample_elements": n1},
                                "host_cpus": os.cpu_count()}
     print(json.dumps(out))

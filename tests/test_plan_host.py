@@ -138,3 +138,29 @@ def test_device_calls_reject_bad_arguments_before_touching_the_gpu(paro):
     assert code(paro.paro_step_fused, pl, 0, [ok] * 4, paro.PARO_CHUNK, hp_clip, 0, ok, ok, ok, ok, ok) == paro.PARO_EINVAL
     mixed = paro.paro_plan(4, 2, "IIG", [64, 64], grad_dtype=[0, 1])
     assert code(paro.paro_reduce_shard, mixed, 0, [ok] * 4, paro.PARO_CHUNK, ok, ok) == paro.PARO_EINVAL
+
+
+def test_ring_and_collective_calls_reject_bad_arguments(paro):
+    pl = paro.paro_plan(4, 2, "IIG", [4096])
+    ok = 1 << 20
+
+    def code(fn, *a):
+        with pytest.raises(paro.ParoError) as ei:
+            fn(*a)
+        return ei.value.code
+    assert code(paro.paro_ring_hop, pl, 0, 0, ok, 0, ok, 8) == paro.PARO_EINVAL
+    assert code(paro.paro_ring_hop, pl, ok, 0, ok + 2, 0, ok, 8) == paro.PARO_EALIGN
+    assert code(paro.paro_ring_hop, pl, ok, 3, ok, 0, ok, 8) == paro.PARO_EINVAL
+    assert code(paro.paro_ring_hop, pl, ok, 0, ok, 1, ok, -1) == paro.PARO_EINVAL
+    assert code(paro.paro_ring_hop, pl, ok, 0, ok * 2, 1, ok, 8) == paro.PARO_EINVAL      # out aliases a bf16 operand
+    assert code(paro.paro_ring_hop, pl, ok, 2, ok * 2, 1, ok, 8) == paro.PARO_EINVAL      # ... or an fp16 one
+    bufs = [ok] * 4
+    assert code(paro.paro_collective_step, pl, 4, paro.PARO_RING, paro.PARO_RS, 1, 0, 1, bufs) == paro.PARO_ERANGE
+    assert code(paro.paro_collective_step, pl, 0, 9, paro.PARO_RS, 1, 0, 1, bufs) == paro.PARO_EINVAL
+    assert code(paro.paro_collective_step, pl, 0, paro.PARO_RING, 7, 1, 0, 1, bufs) == paro.PARO_EINVAL
+    assert code(paro.paro_collective_step, pl, 0, paro.PARO_RING, paro.PARO_RS, 1, 0, 1, [ok, 0, ok, ok]) == paro.PARO_EINVAL
+    assert code(paro.paro_collective_step, pl, 0, paro.PARO_RING, paro.PARO_AG, 1, 0, 1, [ok, ok + 8, ok, ok]) == paro.PARO_EALIGN
+    hp = paro.make_adam(lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, grad_scale=0.25,
+                        skip_nonfinite=True)
+    assert code(paro.paro_adam_shard, pl, 0, hp, ok, 0, ok, ok, ok, 0) == paro.PARO_EINVAL          # needs the total
+    assert code(paro.paro_step_fused, pl, 0, [ok] * 4, paro.PARO_CHUNK, hp, 0, ok, ok, ok, ok, ok) == paro.PARO_EINVAL
