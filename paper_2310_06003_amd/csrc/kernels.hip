@@ -399,6 +399,18 @@ __device__ __forceinline__ void locate8(const TileSegs &segs, int rel0, Where8 &
     int c = segs.find(rel0);
     const int n = segs.count();
     const int c_first = c;
+    if (c >= 0 && (int64_t)(rel0 + 7) < segs.s_off[c + 1]) {      // the usual case: all 8 in one segment
+        const int t = segs.tm.nz_tensor[segs.first() + c];
+        const int64_t toff = (int64_t)rel0 - segs.s_off[c];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            w.tens[i] = t;
+            w.toff[i] = toff + i;
+        }
+        w.one_tensor = true;
+        w.first_dt = segs.tm.dtype[t];
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int rel = rel0 + i;
