@@ -1,0 +1,63 @@
+"""The fused step inside a HIP graph: the device entry points only enqueue kernels on the
+caller's stream (no allocation, no synchronisation, no memset after the plan's first device
+call), so a captured step must replay to the eager result, every time."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from harness import DEV, hp_dict, hp_struct, np_of
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("max_norm", [0.0, 0.01])
+def test_fused_step_replays_from_a_graph(paro, max_norm):
+    P, G, strategy, rank = 8, 4, "IIG", 3
+    sizes = [P * 2048 * 40 + 24]
+    pl = paro.paro_plan(P, G, strategy, sizes)
+    L = paro.paro_shard_len(pl)
+    contrib = wl.chunk_contribs(P, L, 5, device=DEV)
+    ptrs = [t.data_ptr() for t in contrib]
+    hp = hp_dict(P, max_norm=max_norm)
+    hs = hp_struct(paro, hp, 3)
+    dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
+
+    def state():
+        p, m, v = wl.master_state(L, 5, device=DEV)
+        return dict(p=p, m=m, v=v, dst=torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV),
+                    g=torch.empty(L, dtype=torch.float32, device=DEV),
+                    ss=torch.zeros(1, dtype=torch.float64, device=DEV))
+
+    def step(s, stream):
+        paro.paro_step_fused(pl, rank, ptrs, paro.PARO_CHUNK, hs, s["g"].data_ptr(), s["ss"].data_ptr(),
+                             s["p"].data_ptr(), s["m"].data_ptr(), s["v"].data_ptr(), s["dst"].data_ptr(), stream)
+
+    # eager: three steps in a row, the state after each kept
+    eager = state()
+    step(eager, torch.cuda.current_stream().cuda_stream)      # also creates the plan's device tables
+    want = []
+    ref = state()
+    for _ in range(3):
+        step(ref, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        want.append({k: np_of(ref[k]).tobytes() for k in ("p", "m", "v", "dst")})
+
+    graphed = state()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        step(graphed, side.cuda_stream)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    # capture enqueues nothing: the state is still the initial one
+    assert np_of(graphed["p"]).tobytes() == np_of(state()["p"]).tobytes()
+    for k in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        _ = float(graphed["ss"].item())                         # eager work and a sync between replays
+        got = {name: np_of(graphed[name]).tobytes() for name in ("p", "m", "v", "dst")}
+        assert got == want[k], f"replay {k + 1} differs from the eager step"
