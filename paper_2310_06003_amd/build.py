@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SO = os.path.join(HERE, "libparo.so")
 SOURCES = [os.path.join(HERE, "csrc", "plan.cpp"), os.path.join(HERE, "csrc", "kernels.hip")]
-HEADERS = [os.path.join(HERE, "csrc", "plan.hpp"), os.path.join(ROOT, "include", "paro.h")]
+HEADERS = [os.path.join(HERE, "csrc", h) for h in ("plan.hpp", "device_util.hpp", "loaders.hpp")] + \
+          [os.path.join(ROOT, "include", "paro.h")]
 
 # -ffp-contract=off: every fp32 operation of the fold and of Adam is rounded on its own, so
 #   results do not depend on which multiply-adds the compiler could fuse.
