@@ -72,7 +72,9 @@ def main():
     import numpy as np
     import torch
 
-    import paper_2310_06003_amd as paro        # raises if libparo.so has not been built
+    from __graft_entry__ import ensure_built
+    ensure_built()                             # builds libparo.so only if it has never been built
+    import paper_2310_06003_amd as paro        # raises if there is no library: no fallback path
     import workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -14,6 +14,9 @@ def pytest_configure(config):
 
 @pytest.fixture(scope="session")
 def paro():
-    """The product binding; GPU tests fail loudly when the HIP library is absent."""
+    """The product binding.  The library is built first if it has never been built; if that
+    fails the import below raises - there is no fallback to run the tests against."""
+    from __graft_entry__ import ensure_built
+    ensure_built()
     import paper_2310_06003_amd as paro_mod
     return paro_mod
