@@ -28,6 +28,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <new>
 #include <cstring>
 #include <string>
 #include <type_traits>
@@ -355,7 +356,12 @@ int ensure_device(paro_plan_t *pl) {
     // per-tile summaries for chunk-aligned launches over the tensor layout (16 B per 2048 elements)
     d.tiles_per_chunk = (pl->L + TILE - 1) / TILE;
     if (pl->T > 1 && (int64_t)pl->P * d.tiles_per_chunk <= (int64_t)4 << 20) {
-        std::vector<paro_tile_info> tab((size_t)pl->P * d.tiles_per_chunk);
+        std::vector<paro_tile_info> tab;
+        try {
+            tab.resize((size_t)pl->P * d.tiles_per_chunk);
+        } catch (const std::bad_alloc &) {
+            return fail(PARO_ENOMEM, "out of host memory while building the per-tile table");
+        }
         const int64_t n_nz = (int64_t)pl->nz_tensor.size();
         for (int c = 0; c < pl->P; ++c) {
             for (int64_t i = 0; i < d.tiles_per_chunk; ++i) {
@@ -752,7 +758,12 @@ int64_t paro_collective_step(paro_plan_t *pl, int rank, int sched, int collectiv
         if ((rc = check_ptr(bufs[q], "paro_collective_step: a buffer"))) return rc;
     const int64_t count = paro_schedule(pl, rank, sched, collective, nullptr, 0);
     if (count < 0) return count;
-    std::vector<paro_msg_t> msgs((size_t)count);
+    std::vector<paro_msg_t> msgs;
+    try {
+        msgs.resize((size_t)count);
+    } catch (const std::bad_alloc &) {
+        return fail(PARO_ENOMEM, "paro_collective_step: out of host memory");
+    }
     if (count && paro_schedule(pl, rank, sched, collective, msgs.data(), count) < 0) return PARO_EINVAL;
     if ((rc = ensure_device(pl))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
