@@ -335,19 +335,18 @@ int upload(T **dst, const T *src, size_t n) {
     return PARO_OK;
 }
 
-// Creates the plan's device tables on the current device, once.
-int ensure_device(paro_plan_t *pl) {
-    std::lock_guard<std::mutex> lock(pl->dev_mutex);
-    int dev = -1;
-    PARO_HIP(hipGetDevice(&dev));
-    if (pl->dev.device >= 0) {
-        if (pl->dev.device != dev)
-            return fail(PARO_EINVAL, "the plan's device tables live on another device than the current one");
-        return PARO_OK;
-    }
-    paro_device_tables d;
-    PARO_HIP(hipDeviceGetAttribute(&d.n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    if (d.n_cu < 1) d.n_cu = 256;
+void free_tables(paro_device_tables &d) {
+    // best effort: at process exit the runtime may already be gone
+    (void)hipFree(d.nz_off);
+    (void)hipFree(d.nz_tensor);
+    (void)hipFree(d.dtype);
+    (void)hipFree(d.no_decay);
+    (void)hipFree(d.tile_tab);
+    (void)hipFree(d.partials);
+    d = paro_device_tables();
+}
+
+int fill_tables(const paro_plan_t *pl, paro_device_tables &d) {
     int rc;
     if ((rc = upload(&d.nz_off, pl->nz_off.data(), pl->nz_off.size()))) return rc;
     if ((rc = upload(&d.nz_tensor, pl->nz_tensor.data(), pl->nz_tensor.size()))) return rc;
@@ -383,13 +382,34 @@ int ensure_device(paro_plan_t *pl) {
         }
         if ((rc = upload(&d.tile_tab, tab.data(), tab.size()))) return rc;
     }
-    // one partial per block of the largest sweep-1 launch (a launch covers one chunk of L elements)
-    // (a launch covers one chunk of L elements), followed by room for the second-level sums
+    // one partial per block of the largest sweep-1 launch (a launch covers one chunk of L elements),
+    // followed by room for the second-level sums
     int64_t n_part = (pl->L + TILE - 1) / TILE;
     if (n_part < PARO_MAX_PARTIALS) n_part = PARO_MAX_PARTIALS;
     d.n_partials = n_part;
     const int64_t n_level2 = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
     PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), (n_part + n_level2) * sizeof(double)));
+    return PARO_OK;
+}
+
+// Creates the plan's device tables on the current device, once.
+int ensure_device(paro_plan_t *pl) {
+    std::lock_guard<std::mutex> lock(pl->dev_mutex);
+    int dev = -1;
+    PARO_HIP(hipGetDevice(&dev));
+    if (pl->dev.device >= 0) {
+        if (pl->dev.device != dev)
+            return fail(PARO_EINVAL, "the plan's device tables live on another device than the current one");
+        return PARO_OK;
+    }
+    paro_device_tables d;
+    PARO_HIP(hipDeviceGetAttribute(&d.n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (d.n_cu < 1) d.n_cu = 256;
+    const int rc = fill_tables(pl, d);
+    if (rc != PARO_OK) {
+        free_tables(d);                    // nothing half-built stays behind
+        return rc;
+    }
     d.device = dev;
     pl->dev = d;
     return PARO_OK;
@@ -604,15 +624,7 @@ extern "C" {
 
 void paro_plan_destroy(paro_plan_t *pl) {
     if (!pl) return;
-    if (pl->dev.device >= 0) {
-        // frees are best effort: the plan may outlive the HIP runtime at process exit
-        (void)hipFree(pl->dev.nz_off);
-        (void)hipFree(pl->dev.nz_tensor);
-        (void)hipFree(pl->dev.dtype);
-        (void)hipFree(pl->dev.no_decay);
-        (void)hipFree(pl->dev.partials);
-        if (pl->dev.tile_tab) (void)hipFree(pl->dev.tile_tab);
-    }
+    if (pl->dev.device >= 0) free_tables(pl->dev);
     delete pl;
 }
 
