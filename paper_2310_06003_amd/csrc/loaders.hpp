@@ -13,11 +13,11 @@ namespace {
 
 struct TileSegs;
 
-// Contributions are arrays in shard coordinates, all bf16 or all fp32.
+// Contributions are arrays in shard coordinates, all of one dtype (bf16, fp16 or fp32).
 template <int DT>
 struct ChunkLoader {
     static constexpr bool kTensor = false;
-    // contributions loaded before the first is consumed (16 bytes each for bf16, 32 for fp32)
+    // contributions loaded before the first is consumed (16 bytes each for the 2-byte dtypes, 32 for fp32)
     static constexpr int kBatch = DT != PARO_F32 ? PARO_BATCH_BF16 : 8;
     struct Raw { u32x4 a, b; };
     int64_t e;                                   // first of the thread's 8 elements

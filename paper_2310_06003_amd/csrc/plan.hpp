@@ -53,7 +53,7 @@ struct paro_plan_s {
     paro_device_tables dev;             // filled on the first device call
 };
 
-enum { PARO_MAX_PARTIALS = 4096 };
+enum { PARO_MAX_PARTIALS = 4096 };   // smallest partial-sum scratch; also the cap on a persistent grid
 
 namespace paro {
 int fail(int code, const std::string &msg);     // records the thread's last error, returns code
