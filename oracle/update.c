@@ -173,6 +173,43 @@ void orc_bf16_rne(const float *p, int64_t n, uint16_t *out) {
     }
 }
 
+/* ---- pack: fp32 -> fp16 (binary16), round to nearest, ties to even ----------
+ * The IEEE definition written out on the bit fields: a value is
+ * 2^(E-127) * S / 2^23 with the 24-bit significand S (hidden bit included);
+ * binary16 keeps 11 significand bits down to exponent -14 and fewer below it
+ * (gradual underflow), so S loses 13 bits, or more for a subnormal result; the
+ * dropped bits decide the rounding; a carry out of the significand moves into
+ * the exponent by plain addition; anything at or beyond 65520 becomes infinity.
+ * NaN becomes a quiet NaN of the same sign (its payload is not kept). */
+static uint16_t f16_rne_one(uint32_t u) {
+    const uint32_t sign = (u >> 16) & 0x8000u, a = u & 0x7FFFFFFFu;
+    if (a > 0x7F800000u) return (uint16_t)(sign | 0x7E00u);
+    const int E = (int)(a >> 23);
+    if (E == 0) return (uint16_t)sign;                 /* fp32 subnormals are far below half of the smallest binary16 */
+    const int e = E - 127;
+    if (e > 15) return (uint16_t)(sign | 0x7C00u);     /* includes infinity */
+    const uint32_t S = (a & 0x7FFFFFu) | 0x800000u;
+    int drop = 13;
+    if (e < -14) drop += -14 - e;                      /* subnormal result: fewer bits survive */
+    if (drop > 25) return (uint16_t)sign;              /* below half of the smallest subnormal */
+    uint32_t q = S >> drop;
+    const uint32_t rem = S & ((1u << drop) - 1u), half = 1u << (drop - 1);
+    if (rem > half || (rem == half && (q & 1u))) q++;
+    /* normal: q in [0x400, 0x800]; exponent field e+15 with the hidden bit of q counted once */
+    uint32_t h = e < -14 ? q : ((uint32_t)(e + 14) << 10) + q;
+    if (h > 0x7C00u) h = 0x7C00u;
+    return (uint16_t)(sign | h);
+}
+
+void orc_f16_rne(const float *p, int64_t n, uint16_t *out) {
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < n; e++) {
+        uint32_t u;
+        memcpy(&u, &p[e], 4);
+        out[e] = f16_rne_one(u);
+    }
+}
+
 int orc_max_threads(void) {
 #ifdef _OPENMP
     extern int omp_get_max_threads(void);

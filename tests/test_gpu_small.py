@@ -215,6 +215,33 @@ def test_pack_special_values(paro):
     assert np_of(dst).tobytes() == orc.bf16_rne(x.view(np.float32)).tobytes()
 
 
+@pytest.mark.parametrize("fmt", [wl.BF16, wl.F16])
+def test_pack_every_fp32_bit_pattern(paro, fmt):
+    """All 2^32 fp32 bit patterns through the pack, in blocks of 2^27: bit-exact
+    against the oracle's rounding.  For fp16 the payload of a NaN is not part of the
+    contract: a NaN must come out as a NaN of the same sign."""
+    n = 1 << 27
+    pl = paro.paro_plan(1, 1, "GGG", [n], pack_dtype=fmt)
+    low = torch.arange(n, dtype=torch.int32, device=DEV)
+    low_h = np.arange(n, dtype=np.uint32)
+    dst = torch.zeros(n, dtype=torch.int16, device=DEV)
+    for b in range(32):
+        hi = b << 27
+        bits = low | (hi - (1 << 32) if hi >= (1 << 31) else hi)
+        p = bits.view(torch.float32)
+        paro.paro_pack_params(pl, 0, p.data_ptr(), dst.data_ptr(), stream())
+        got = dst.cpu().numpy().view(np.uint16)
+        x = (low_h | np.uint32(hi)).view(np.float32)
+        if fmt == wl.BF16:
+            assert got.tobytes() == orc.bf16_rne(x).tobytes(), f"bf16 pack differs in block {b}"
+        else:
+            ref = orc.f16_rne(x)
+            nan = np.isnan(x)
+            assert (got[~nan] == ref[~nan]).all(), f"fp16 pack differs in block {b}"
+            g_nan = got[nan]
+            assert ((g_nan & 0x7FFF) > 0x7C00).all() and ((g_nan >> 15) == (ref[nan] >> 15)).all()
+
+
 def test_runs_are_bit_identical(paro):
     P, G = 16, 8
     sizes = [16 * 3 * 2048 * 11]

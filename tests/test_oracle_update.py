@@ -281,12 +281,25 @@ def test_f16_pack_matches_torch_cast():
         x = (hi | np.uint32(lo)).view(np.float32)
         got = orc.f16_rne(x)
         want = torch.from_numpy(x).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+        with np.errstate(over="ignore", under="ignore"):
+            want_np = x.astype(np.float16).view(np.uint16)             # a second, unrelated implementation
         nan = np.isnan(x)
-        assert (got[~nan] == want[~nan]).all()
+        assert (got[~nan] == want[~nan]).all() and (got[~nan] == want_np[~nan]).all()
         assert ((got[nan] & 0x7C00) == 0x7C00).all() and ((got[nan] & 0x03FF) != 0).all()
+        assert ((got[nan] >> 15) == (x[nan].view(np.uint32) >> 31)).all()
     f = lambda v: int(orc.f16_rne(np.array([v], np.float32))[0])       # noqa: E731
     assert f(65504.0) == 0x7BFF and f(65520.0) == 0x7C00 and f(65519.9) == 0x7BFF    # overflow threshold
     assert f(2.0 ** -24) == 0x0001 and f(2.0 ** -25) == 0x0000 and f(1.5 * 2.0 ** -25) == 0x0001
+    # every binary16 value converts back to itself, and the midpoint between neighbours goes to the even one
+    h = np.arange(0x7C00, dtype=np.uint16)
+    vals = h.view(np.float16).astype(np.float32)
+    assert (orc.f16_rne(vals) == h).all() and (orc.f16_rne(-vals) == (h | 0x8000)).all()
+    mid = ((vals[:-1].astype(np.float64) + vals[1:].astype(np.float64)) / 2).astype(np.float32)   # exact in fp32
+    even = np.where(h[:-1] & 1, h[1:], h[:-1])
+    assert (orc.f16_rne(mid) == even).all()
+    above = np.nextafter(mid, np.float32(np.inf))
+    below = np.nextafter(mid, np.float32(-np.inf))
+    assert (orc.f16_rne(above) == h[1:]).all() and (orc.f16_rne(below[1:]) == h[1:-1]).all()
 
 
 def test_fold_of_f16_inputs_is_the_fold_of_their_exact_values():
