@@ -38,6 +38,10 @@ def parse():
     ap.add_argument("--workload", default="llama7b_share",
                     choices=["llama7b_share", "llama65b_share", "tiny_share"])
     ap.add_argument("--no-clip", action="store_true", help="single-sweep path (max_norm = 0)")
+    ap.add_argument("--layout", default="chunk", choices=["chunk", "tensors"],
+                    help="chunk: contributions are buffers in shard coordinates (the default, the configuration the "
+                         "metric is quoted on); tensors: the same shard of the Llama-7B tensor list, each simulated "
+                         "rank handing over per-tensor gradients (llama7b_share only)")
     ap.add_argument("--cpu-sample", type=int, default=0,
                     help="elements of the shard the oracle is timed on with all threads (0 = the whole shard, "
                          "about 10 s of CPU work in all at the default workload)")
@@ -99,18 +103,39 @@ def main():
     P, G, strategy = cfg.P, cfg.G, cfg.strategy
     rank = 5 if P == 16 else (21 if P == 64 else 0)
     max_norm = 0.0 if args.no_clip else cfg.max_norm
-    pl = paro.paro_plan(P, G, strategy, cfg.sizes)
+    sizes = cfg.sizes
+    if args.layout == "tensors":
+        assert args.workload == "llama7b_share", "--layout tensors goes with the llama7b_share workload"
+        sizes = wl.llama7b_sizes()                 # the same Psi as a list of 291 tensors
+    pl = paro.paro_plan(P, G, strategy, sizes)
     L = paro.paro_shard_len(pl)
     ob, ol = paro.paro_range(pl, rank, "O")
     assert ol == L
     dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
 
-    contrib = wl.chunk_contribs(P, L, 7, device=dev)
+    if args.layout == "tensors":
+        # per simulated rank, only the tensors that meet this rank's range exist; the pointer table gives
+        # the others a valid address, which the step never reads
+        sets = wl.tensor_contribs_over_range(P, sizes, ob, ol, 7, device=dev)
+        tables = []
+        for ts in sets:
+            spare = ts.flat[wl.BF16].data_ptr()
+            tables.append(torch.tensor([spare if t is None else t.data_ptr() for t in ts.tensors],
+                                       dtype=torch.int64, device=dev))
+        ptrs = [t.data_ptr() for t in tables]
+        layout = paro.PARO_TENSORS
+        # the same bytes in shard coordinates (for the CPU baseline and the extras)
+        first = next(t for t, x in enumerate(sets[0].tensors) if x is not None)
+        lo = ob - sum(sizes[:first])
+        contrib = [ts.flat[wl.BF16][lo:lo + ol] for ts in sets]
+    else:
+        contrib = wl.chunk_contribs(P, L, 7, device=dev)
+        ptrs = [t.data_ptr() for t in contrib]
+        layout = paro.PARO_CHUNK
     p, m, v = wl.master_state(L, 7, device=dev)
     dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=dev)
     g = torch.empty(L, dtype=torch.float32, device=dev)
     ss = torch.zeros(1, dtype=torch.float64, device=dev)
-    ptrs = [t.data_ptr() for t in contrib]
     hp = dict(wl.ADAM_DEFAULT, grad_scale=1.0 / P, max_norm=max_norm, adamw=True)
     st = torch.cuda.current_stream().cuda_stream
 
@@ -119,7 +144,7 @@ def main():
         if max_norm > 0:
             if ev:
                 ev[0].record()
-            paro.paro_reduce_shard(pl, rank, ptrs, paro.PARO_CHUNK, g.data_ptr(), ss.data_ptr(), st)
+            paro.paro_reduce_shard(pl, rank, ptrs, layout, g.data_ptr(), ss.data_ptr(), st)
             if ev:
                 ev[1].record()
             paro.paro_adam_shard(pl, rank, hs, g.data_ptr(), ss.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(),
@@ -129,14 +154,14 @@ def main():
         else:
             if ev:
                 ev[0].record()
-            paro.paro_step_fused(pl, rank, ptrs, paro.PARO_CHUNK, hs, 0, 0, p.data_ptr(), m.data_ptr(), v.data_ptr(),
+            paro.paro_step_fused(pl, rank, ptrs, layout, hs, 0, 0, p.data_ptr(), m.data_ptr(), v.data_ptr(),
                                  dst.data_ptr(), st)
             if ev:
                 ev[1].record()
                 ev[2].record()
 
     def fused_step(k):
-        paro.paro_step_fused(pl, rank, ptrs, paro.PARO_CHUNK, paro.make_adam(step=k, **hp), g.data_ptr(),
+        paro.paro_step_fused(pl, rank, ptrs, layout, paro.make_adam(step=k, **hp), g.data_ptr(),
                              ss.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(), st)
 
     K, W = args.steps, args.warmup
@@ -167,7 +192,7 @@ def main():
     bytes_dom = (2 * P + (4 if clip else 26)) * L
     dom_ms = ms1
     achieved = bytes_dom / (dom_ms * 1e-3) / 1e9
-    traffic = measured_traffic(args.workload) if clip else None
+    traffic = measured_traffic(args.workload) if clip and args.layout == "chunk" else None
     out = {
         "metric": "shard_params_updated_per_s (fused reduce+Adam+pack step)",
         "value": L / (ms_step * 1e-3),
@@ -181,7 +206,7 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": args.workload, "P": P, "G": G, "strategy": strategy,
+        "config": {"workload": args.workload, "layout": args.layout, "P": P, "G": G, "strategy": strategy,
                    "schedule": ["ring", "h-ring", "ho-ring"][paro.paro_sched(pl)], "rank": rank,
                    "shard_params": L, "contrib_dtype": "bf16", "clip_max_norm": max_norm,
                    "sweeps": 2 if clip else 1},

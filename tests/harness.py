@@ -43,7 +43,9 @@ class PtrTable:
 
     def __init__(self, tensors):
         self.keep = tensors
-        ptrs = [t.data_ptr() if t.numel() else 0 for t in tensors]
+        # an absent tensor (None: outside the range the step covers) gets a valid address all the same
+        spare = next(t for t in tensors if t is not None).data_ptr()
+        ptrs = [spare if t is None else (t.data_ptr() if t.numel() else 0) for t in tensors]
         self.table = torch.tensor(ptrs, dtype=torch.int64, device=DEV)
 
     def ptr(self):

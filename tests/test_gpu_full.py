@@ -17,7 +17,7 @@ import torch
 
 import oracle as orc
 import workloads as wl
-from harness import DEV, compare_step, hp_dict, hp_struct, np_of, oracle_update, stream
+from harness import DEV, PtrTable, compare_step, hp_dict, hp_struct, np_of, oracle_update, stream
 
 pytestmark = pytest.mark.gpu
 
@@ -90,6 +90,69 @@ def test_llama7b_share_full_size(paro):
         g_hat = float(np.float32(hp["grad_scale"])) * coef * g_blocks[lo].astype(np.float64)
         compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"llama7b block at {lo}", literal=lit)
     assert not bool(dst[L:].any()), "the other group's slot of the parameter block must stay untouched"
+
+
+def test_llama7b_share_tensor_layout(paro):
+    """The same shard of the 291-tensor Llama-7B list, each simulated rank handing over
+    per-tensor gradients: the fold and the sum of squares against the oracle on every
+    block that holds a tensor boundary plus random ones, then the fused step on samples."""
+    _need_memory(40)
+    P, G, strategy, rank = 16, 8, "IIG", 5
+    sizes = wl.llama7b_sizes()
+    lay = orc.layout(P, G, sizes)
+    L = lay.L
+    assert len(sizes) == 291 and lay.total == 6_738_415_616 and L == 421_150_976
+    sched = orc.default_sched(P, G)
+    pl = paro.paro_plan(P, G, strategy, sizes)
+    ob, ol = orc.state_range(lay, rank, strategy[2])
+    assert paro.paro_range(pl, rank, "O") == (ob, ol) and ol == L
+    sets = wl.tensor_contribs_over_range(P, sizes, ob, ol, 11, device=DEV)
+    tables = [PtrTable(s.tensors) for s in sets]
+    ptrs = [t.ptr() for t in tables]
+    segs = orc.segments(lay, ob, ol)
+    assert len(segs) >= 10                                    # the range crosses many tensors
+
+    p, m, v = wl.master_state(L, 11, device=DEV)
+    blk = 1 << 22
+    nb = (L + blk - 1) // blk
+    rng = np.random.default_rng(3)
+    picks = {0, nb - 1} | {int(x) for x in rng.integers(0, nb, 4)} | {soff // blk for (_t, _o, soff, _n) in segs}
+    picks = [(b * blk, min(blk, L - b * blk)) for b in sorted(picks)]
+    old = {lo: [np_of(t[lo:lo + n]) for t in (p, m, v)] for lo, n in picks}
+
+    dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
+    dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+    g = torch.empty(L, dtype=torch.float32, device=DEV)
+    ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+    hp = hp_dict(P, max_norm=1.0)
+    paro.paro_step_fused(pl, rank, ptrs, paro.PARO_TENSORS, hp_struct(paro, hp, 1), g.data_ptr(), ss.data_ptr(),
+                         p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(), stream())
+    torch.cuda.synchronize()
+
+    order, gl = orc.fold_order(P, G, sched, orc.chunk_of_rank(rank, P, G))
+    g_blocks = {}
+    for lo, n in picks:
+        gr = np.empty(n, np.float32)
+        for (t, toff, soff, ln) in orc.segments(lay, ob + lo, n):       # the oracle's own map: flat range -> tensors
+            orc.fold([np_of(sets[q].tensors[t][toff:toff + ln]) for q in order], gl, out=gr[soff:soff + ln])
+        assert np_of(g[lo:lo + n]).tobytes() == gr.tobytes(), f"reduced gradient differs in block at {lo}"
+        g_blocks[lo] = gr
+    chk = 0.0
+    for lo in range(0, L, 1 << 27):
+        chk += float(g[lo:lo + (1 << 27)].double().square().sum().item())
+    total = float(ss.item())
+    assert abs(total - chk) <= 1e-11 * chk
+    coef = orc.clip_coef(total, np.float32(hp["grad_scale"]), np.float32(hp["max_norm"]))
+    assert coef < 1.0
+    for lo, n in picks:
+        p0, m0, v0 = old[lo]
+        ref = oracle_update(lay, strategy, rank, g_blocks[lo], p0, m0, v0, total_sumsq=total, hp=hp, step=1)
+        lit = oracle_update(lay, strategy, rank, g_blocks[lo], p0, m0, v0, total_sumsq=total, hp=hp, step=1,
+                            literal32=True)
+        got = dict(p=np_of(p[lo:lo + n]), m=np_of(m[lo:lo + n]), v=np_of(v[lo:lo + n]),
+                   q=np_of(dst[slot_off + lo:slot_off + lo + n]))
+        g_hat = float(np.float32(hp["grad_scale"])) * coef * g_blocks[lo].astype(np.float64)
+        compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"llama7b tensors, block at {lo}", literal=lit)
 
 
 def test_llama65b_share_full_size(paro):

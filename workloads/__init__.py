@@ -53,6 +53,21 @@ def llama7b_total() -> int:
     return llama_total(32, 4096, 11008, 32000)
 
 
+def llama_sizes(layers: int, d: int, ffn: int, vocab: int) -> List[int]:
+    """The tensor list behind llama_total, in model order: the input embedding;
+    per layer a d-vector, four d*d matrices, a d-vector and three d*ffn
+    matrices; the final d-vector and the output embedding."""
+    sizes = [vocab * d]
+    for _ in range(layers):
+        sizes += [d, d * d, d * d, d * d, d * d, d, d * ffn, d * ffn, ffn * d]
+    sizes += [d, vocab * d]
+    return sizes
+
+
+def llama7b_sizes() -> List[int]:
+    return llama_sizes(32, 4096, 11008, 32000)
+
+
 def llama65b_total() -> int:
     return llama_total(80, 8192, 22016, 32000)
 
@@ -190,6 +205,34 @@ def tensor_contribs(P: int, sizes: List[int], dtypes: Optional[List[int]], base_
             k = dtypes[t] if dtypes is not None else BF16
             per.append(flat[k][start[t]:start[t] + n])
         out.append(TensorSet(per, flat, start))
+    return out
+
+
+def tensor_contribs_over_range(P: int, sizes: List[int], begin: int, length: int, base_seed: int, step: int = 0, *,
+                               dist="normal", device="cpu") -> List[TensorSet]:
+    """Like tensor_contribs for all-bf16 lists too large to hold P times: per
+    simulated rank only the tensors that meet flat elements [begin, begin+length)
+    exist (whole, packed back to back); tensors[t] is None for the others, which a
+    step over that range never reads."""
+    first, last, off = None, None, 0
+    offs = []
+    for t, n in enumerate(sizes):
+        offs.append(off)
+        if n and off < begin + length and off + n > begin:
+            first = t if first is None else first
+            last = t
+        off += n
+    assert first is not None
+    span = offs[last] + sizes[last] - offs[first]
+    out = []
+    for q in range(P):
+        flat = draw(span, _seed(base_seed, step, q, salt=1), dist=dist, dtype=BF16, device=device)
+        per: List[Optional[torch.Tensor]] = [None] * len(sizes)
+        start = [0] * len(sizes)
+        for t in range(first, last + 1):
+            start[t] = offs[t] - offs[first]
+            per[t] = flat[start[t]:start[t] + sizes[t]]
+        out.append(TensorSet(per, {BF16: flat}, start))
     return out
 
 
