@@ -314,6 +314,46 @@ def test_tensor_layout_small_ragged(paro):
                     lit_state[rank] = [lit["p"], lit["m"], lit["v"]]
 
 
+@pytest.mark.parametrize("P,G,strategy", [(256, 16, "IGG"), (64, 8, "NIG"), (12, 3, "IIG")])
+def test_tensor_layout_many_ranks(paro, P, G, strategy):
+    """Tensor layout at large P (the pointer staging covers up to 256 sources), shards of a
+    few tiles that hold both whole-tensor tiles and tiles with boundaries; sampled ranks."""
+    rng = np.random.default_rng(P)
+    sizes = [int(s) for s in rng.integers(1, 30, 25)] + [40000, 3, 8192, 2048 * 9, 77, 1_500_000, 123456, 5]
+    dtypes = [int(x) for x in rng.choice([wl.BF16, wl.F32, wl.F16], len(sizes))]
+    lay = orc.layout(P, G, sizes)
+    sched = orc.default_sched(P, G)
+    pl = paro.paro_plan(P, G, strategy, sizes, grad_dtype=dtypes)
+    sets = wl.tensor_contribs(P, sizes, dtypes, 70, 1, device=DEV)
+    tables = [PtrTable(s.tensors) for s in sets]
+    host = [[np_of(t) for t in s.tensors] for s in sets]
+    n = P * lay.L
+    state = [np_of(t) for t in wl.master_state(n, 71)]
+    for a in state:
+        a[lay.total:] = 0
+    hp = hp_dict(P, max_norm=0.001)
+    for rank in sorted({0, 1, G, P // 2 + 1, P - 1}):
+        ob, ol = orc.state_range(lay, rank, strategy[2])
+        g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, host, "tensors")
+        old = [a[ob:ob + ol].copy() for a in state]
+        ref = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=1)
+        lit = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=1, literal32=True)
+        p, m, v = (torch.from_numpy(a.copy()).to(DEV) for a in old)
+        dst_len, slot_off, slot_len = orc.pack_slot(lay, rank, strategy)
+        dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+        gs = torch.empty(ol, dtype=torch.float32, device=DEV)
+        ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+        paro.paro_step_fused(pl, rank, [t.ptr() for t in tables], paro.PARO_TENSORS, hp_struct(paro, hp, 1),
+                             gs.data_ptr(), ss.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(),
+                             stream())
+        what = f"P{P} {strategy} rank{rank}"
+        assert np_of(gs).tobytes() == g_ref.tobytes(), what
+        assert abs(float(ss.item()) - ss_ref) <= 1e-12 * ss_ref and ref["coef"] < 1.0
+        g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
+        got = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=np_of(dst)[slot_off:slot_off + slot_len])
+        compare_step(got, ref, p_old=old[0], m_old=old[1], g_hat=g_hat, what=what, literal=lit)
+
+
 def _rng(lay, rank, strategy):
     ob, ol = orc.state_range(lay, rank, strategy[2])
     return ob, ob + ol
