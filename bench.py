@@ -12,7 +12,8 @@ entry point is timed right after as a cross-check.
 Prints ONE JSON line.  `value` = shard parameters updated per second.
 `roofline` is for the dominant kernel (sweep 1, the fold): algorithmic bytes
 (2P + 4 per parameter: P bf16 reads, one fp32 write) over its mean duration,
-against 8 TB/s.  `cpu_baseline` times the CPU oracle on a bounded sample of the
+against 8 TB/s; `copy_ref` is what a plain device copy of 3.4 GB reaches in the same
+process (`roofline.frac_of_copy` = the fold's rate over the copy's).  `cpu_baseline` times the CPU oracle on a bounded sample of the
 same buffers on this machine's host cores (a baseline, not a target).
 """
 from __future__ import annotations
@@ -225,18 +226,33 @@ def main():
     if clip:
         out["kernels"]["sweep2_adam_pack"] = {"ms": ms2, "bytes_per_param": 30, "gbps": 30 * L / (ms2 * 1e-3) / 1e9}
 
-    if args.extras:
-        def timed(fn, reps=10):
+    def timed(fn, reps=10):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
             fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / reps
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
 
+    # what a plain copy reaches on this machine, same process: the library's own copy kernel (the all-gather
+    # landing copy) moving a message of 2L bf16 elements = as many bytes as g holds, each way
+    cp = paro.paro_plan(2, 2, "NGG", [4 * L])
+    assert paro.paro_shard_len(cp) == 2 * L
+    ca = torch.zeros(4 * L, dtype=torch.bfloat16, device=dev)
+    cb = torch.ones(4 * L, dtype=torch.bfloat16, device=dev)
+    ms_copy = timed(lambda: paro.paro_collective_step(cp, 0, paro.PARO_RING, paro.PARO_AG, 1, 0, 1,
+                                                      [ca.data_ptr(), cb.data_ptr()], st))
+    copy_gbps = 8 * L / (ms_copy * 1e-3) / 1e9
+    del ca, cb
+    out["copy_ref"] = {"kernel": "k_copy16", "bytes_read": 4 * L, "bytes_written": 4 * L, "ms": ms_copy,
+                       "gbps": copy_gbps}
+    out["roofline"]["frac_of_copy"] = achieved / copy_gbps
+    out["hbm_frac_of_copy_step"] = out["hbm_gbps_step"] / copy_gbps
+
+    if args.extras:
         wire = torch.zeros(L, dtype=torch.float32, device=dev)          # partial arriving over the ring (fp32)
         ms_hop = timed(lambda: paro.paro_ring_hop(pl, wire.data_ptr(), paro.PARO_F32, contrib[0].data_ptr(),
                                                   paro.PARO_BF16, g.data_ptr(), L, st))

@@ -35,6 +35,21 @@ namespace {
 #ifndef PARO_BLOCKS_PER_CU
 #define PARO_BLOCKS_PER_CU 8
 #endif
+#ifndef PARO_FOLD4
+#define PARO_FOLD4 1        // sweep 1, chunk layout: the 4-elements-per-thread kernel
+#endif
+#ifndef PARO_FOLD4_TPB
+#define PARO_FOLD4_TPB 64   // its block size (one wave)
+#endif
+#ifndef PARO_ADAM4
+#define PARO_ADAM4 1        // sweep 2 without a decay mask: the 4-elements-per-thread kernel
+#endif
+#ifndef PARO_NT_ADAM4
+#define PARO_NT_ADAM4 3     // its cache policy: bit 0 streaming loads, bit 1 streaming stores
+#endif
+#ifndef PARO_ADAM4_TPB
+#define PARO_ADAM4_TPB 64   // its block size (one wave)
+#endif
 #ifndef PARO_BATCH_BF16
 #define PARO_BATCH_BF16 16
 #endif
@@ -49,6 +64,7 @@ constexpr int BLOCKS_PER_CU = PARO_BLOCKS_PER_CU;
 constexpr int FINALIZE_CHUNK = 2048;  // partials per block in the first level of the final sum
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // P device pointers in fold order.  Lives in the kernel-argument segment and is
@@ -190,20 +206,25 @@ __device__ __forceinline__ void store8_f32_wave_contiguous(float *wave_base, con
 }
 
 // Sum over the block, valid in thread 0.  Fixed shape: lanes by shuffles, then
-// the four waves in order.
+// the waves in order.
+template <int NTHREADS = TPB>
 __device__ __forceinline__ double block_sum(double v) {
-    __shared__ double s_wave[TPB / 64];
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (lane == 0) s_wave[wave] = v;
-    __syncthreads();
-    double r = 0.0;
-    if (threadIdx.x == 0) {
-        r = s_wave[0];
-        for (int w = 1; w < TPB / 64; ++w) r += s_wave[w];
+    if constexpr (NTHREADS == 64) {
+        return v;
+    } else {
+        __shared__ double s_wave[NTHREADS / 64];
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        if (lane == 0) s_wave[wave] = v;
+        __syncthreads();
+        double r = 0.0;
+        if (threadIdx.x == 0) {
+            r = s_wave[0];
+            for (int w = 1; w < NTHREADS / 64; ++w) r += s_wave[w];
+        }
+        __syncthreads();
+        return r;
     }
-    __syncthreads();
-    return r;
 }
 
 template <class Ld>

@@ -17,6 +17,7 @@ struct TileSegs;
 template <int DT>
 struct ChunkLoader {
     static constexpr bool kTensor = false;
+    static constexpr int kElems = 8;
     // contributions loaded before the first is consumed (16 bytes each for the 2-byte dtypes, 32 for fp32)
     static constexpr int kBatch = DT != PARO_F32 ? PARO_BATCH_BF16 : 8;
     struct Raw { u32x4 a, b; };
@@ -43,6 +44,33 @@ struct ChunkLoader {
             x[2] = __uint_as_float(r.a.z); x[3] = __uint_as_float(r.a.w);
             x[4] = __uint_as_float(r.b.x); x[5] = __uint_as_float(r.b.y);
             x[6] = __uint_as_float(r.b.z); x[7] = __uint_as_float(r.b.w);
+        }
+    }
+};
+
+// The same contributions taken 4 elements per thread: an 8-byte load per contribution for the
+// 2-byte dtypes (a wave instruction covers 512 consecutive bytes), a 16-byte load for fp32.
+template <int DT>
+struct Chunk4Loader {
+    static constexpr bool kTensor = false;
+    static constexpr int kElems = 4;
+    static constexpr int kBatch = PARO_BATCH_BF16;
+    using Raw = std::conditional_t<DT == PARO_F32, u32x4, u32x2>;
+    int64_t e;                                   // first of the thread's 4 elements
+    template <bool SLOW>
+    __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
+        if constexpr (DT != PARO_F32)
+            r = ld_contrib(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(src.p[k]) + e));
+        else
+            r = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const float *>(src.p[k]) + e));
+    }
+    template <bool SLOW>
+    __device__ __forceinline__ void unpack(const SrcTable &, int, const Raw &r, float x[4]) const {
+        if constexpr (DT != PARO_F32) {
+            x[0] = cvt_lo<DT>(r.x); x[1] = cvt_hi<DT>(r.x); x[2] = cvt_lo<DT>(r.y); x[3] = cvt_hi<DT>(r.y);
+        } else {
+            x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y);
+            x[2] = __uint_as_float(r.z); x[3] = __uint_as_float(r.w);
         }
     }
 };
@@ -191,6 +219,7 @@ __device__ __forceinline__ void locate8(const TileSegs &segs, int rel0, Where8 &
 // mapped memory.  Slow path (a tensor boundary or padding inside the 8): element loads.
 struct TensorLoader {
     static constexpr bool kTensor = true;
+    static constexpr int kElems = 8;
     static constexpr int kBatch = 4;
     struct Raw { u32x4 a, b, c, meta; };      // meta.x = byte offset of the first wanted byte in block a
     const uint8_t *dtype;  // [T]
@@ -303,6 +332,7 @@ struct TensorLoader {
 template <int DT>
 struct Staged16Loader {
     static constexpr bool kTensor = false;
+    static constexpr int kElems = 8;
     static constexpr int kBatch = PARO_BATCH_BF16;
     struct Raw { u32x4 a; };
     const uintptr_t *s_ptr;
@@ -318,14 +348,16 @@ struct Staged16Loader {
 };
 
 // ---------------------------------------------------------------------- fold
+// (named for its first use: it folds Ld::kElems elements per thread)
 // X[i] = contributions added in table order: runs of group_len into a partial A
 // (left to right), partials into X (left to right).  The first value of a run
 // and the first partial are copied, not added to zero (that would lose -0).
 // SLOW (tensor layout only): some thread of the wave has a tensor boundary inside its 8
 // elements; contributions are then taken one at a time, each thread on its own path.
 template <class Ld, bool SLOW>
-__device__ __forceinline__ void fold8(const Ld &ld, const SrcTable &src, int P, int group_len, float X[8]) {
-    float A[8];
+__device__ __forceinline__ void fold8(const Ld &ld, const SrcTable &src, int P, int group_len, float X[Ld::kElems]) {
+    constexpr int E = Ld::kElems;                // elements per thread: 8, or 4 for the 4-element loaders
+    float A[E];
     int pos = 0;
     bool first_group = true;
     constexpr int FOLD_BATCH = SLOW ? 1 : Ld::kBatch;
@@ -336,24 +368,24 @@ __device__ __forceinline__ void fold8(const Ld &ld, const SrcTable &src, int P, 
         });
         static_for<0, FOLD_BATCH>([&](auto b) {
             if (k0 + b < P) {
-                float x[8];
+                float x[E];
                 ld.template unpack<SLOW>(src, k0 + b, raw[b], x);
                 if (pos == 0) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) A[i] = x[i];
+                    for (int i = 0; i < E; ++i) A[i] = x[i];
                 } else {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) A[i] = A[i] + x[i];
+                    for (int i = 0; i < E; ++i) A[i] = A[i] + x[i];
                 }
                 if (++pos == group_len) {
                     pos = 0;
                     if (first_group) {
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) X[i] = A[i];
+                        for (int i = 0; i < E; ++i) X[i] = A[i];
                         first_group = false;
                     } else {
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) X[i] = X[i] + A[i];
+                        for (int i = 0; i < E; ++i) X[i] = X[i] + A[i];
                     }
                 }
             }
