@@ -41,6 +41,21 @@ namespace {
 #ifndef PARO_FOLD4_TPB
 #define PARO_FOLD4_TPB 64   // its block size (one wave)
 #endif
+#ifndef PARO_FOLD4_WAVES_PER_CU
+#define PARO_FOLD4_WAVES_PER_CU 14   // blocks (waves) of it in flight per compute unit; 0 = no limit
+#endif
+#ifndef PARO_FUSED4_WAVES_PER_CU
+#define PARO_FUSED4_WAVES_PER_CU 10
+#endif
+#ifndef PARO_HOP_WAVES_PER_CU
+#define PARO_HOP_WAVES_PER_CU 0
+#endif
+#ifndef PARO_COPY_WAVES_PER_CU
+#define PARO_COPY_WAVES_PER_CU 0
+#endif
+#ifndef PARO_ADAM4_WAVES_PER_CU
+#define PARO_ADAM4_WAVES_PER_CU 12
+#endif
 #ifndef PARO_ADAM4
 #define PARO_ADAM4 1        // sweep 2 without a decay mask: the 4-elements-per-thread kernel
 #endif

@@ -228,31 +228,33 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
     }
 }
 
-// Sweep 2 when no tensor is exempt from weight decay (nothing to look up per element): 4 elements
-// per thread, so that every load and store instruction of a wave covers 1 KB of consecutive
-// addresses - whole cache lines, which is what lets the streaming policy be used both ways
-// without partial-line writes.
+// ---- 4 elements per thread, one-wave blocks: the shape of the sweeps that need no per-element
+// look-up (chunk layout, no tensor exempt from weight decay).  Every load and store instruction
+// of a wave covers 1 KB of consecutive addresses (512 B for 2-byte data) - whole cache lines,
+// which is what lets the streaming policy be used both ways without partial-line writes.
+constexpr bool ADAM4_LNT = (PARO_NT_ADAM4 & 1) != 0, ADAM4_SNT = (PARO_NT_ADAM4 & 2) != 0;
+
+struct State4 { f32x4 p, m, v; };
+
+__device__ __forceinline__ State4 load_state4(const float *p, const float *m, const float *v, int64_t e) {
+    State4 s;
+    s.p = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(p + e));
+    s.m = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(m + e));
+    s.v = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(v + e));
+    return s;
+}
+
+// Adam on the thread's 4 elements, state and (optionally) the low-precision copy written back.
 template <bool PACK>
-__global__ __launch_bounds__(PARO_ADAM4_TPB) void k_adam4(const AdamConsts a, const double *__restrict__ total_sumsq,
-                                               const float *__restrict__ g, float *__restrict__ p,
-                                               float *__restrict__ m, float *__restrict__ v,
-                                               uint16_t *__restrict__ dst, int64_t n) {
-    if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
-    const float sc = scale_from_norm(a, total_sumsq);
-    const int64_t e = ((int64_t)blockIdx.x * PARO_ADAM4_TPB + threadIdx.x) * 4;      // n is a multiple of 8
-    if (e >= n) return;
-    constexpr bool LNT = (PARO_NT_ADAM4 & 1) != 0, SNT = (PARO_NT_ADAM4 & 2) != 0;
-    const f32x4 G = ld_as<LNT>(reinterpret_cast<const f32x4 *>(g + e));
-    const f32x4 P = ld_as<LNT>(reinterpret_cast<const f32x4 *>(p + e));
-    const f32x4 M = ld_as<LNT>(reinterpret_cast<const f32x4 *>(m + e));
-    const f32x4 V = ld_as<LNT>(reinterpret_cast<const f32x4 *>(v + e));
-    float gg[4] = {G.x, G.y, G.z, G.w}, pp[4] = {P.x, P.y, P.z, P.w}, mm[4] = {M.x, M.y, M.z, M.w},
-          vv[4] = {V.x, V.y, V.z, V.w};
+__device__ __forceinline__ void update4(const AdamConsts &a, float sc, const float gg[4], const State4 &s, float *p,
+                                        float *m, float *v, uint16_t *dst, int64_t e) {
+    float pp[4] = {s.p.x, s.p.y, s.p.z, s.p.w}, mm[4] = {s.m.x, s.m.y, s.m.z, s.m.w},
+          vv[4] = {s.v.x, s.v.y, s.v.z, s.v.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) adam1(a, sc, true, gg[i], pp[i], mm[i], vv[i]);
-    st_as<SNT>(reinterpret_cast<f32x4 *>(p + e), f32x4{pp[0], pp[1], pp[2], pp[3]});
-    st_as<SNT>(reinterpret_cast<f32x4 *>(m + e), f32x4{mm[0], mm[1], mm[2], mm[3]});
-    st_as<SNT>(reinterpret_cast<f32x4 *>(v + e), f32x4{vv[0], vv[1], vv[2], vv[3]});
+    st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(p + e), f32x4{pp[0], pp[1], pp[2], pp[3]});
+    st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(m + e), f32x4{mm[0], mm[1], mm[2], mm[3]});
+    st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(v + e), f32x4{vv[0], vv[1], vv[2], vv[3]});
     if (PACK) {
         u32x2 w;
         if (a.pack_dtype == PARO_F16) {
@@ -262,8 +264,39 @@ __global__ __launch_bounds__(PARO_ADAM4_TPB) void k_adam4(const AdamConsts a, co
             w.x = f32_to_bf16_rne(pp[0]) | (f32_to_bf16_rne(pp[1]) << 16);
             w.y = f32_to_bf16_rne(pp[2]) | (f32_to_bf16_rne(pp[3]) << 16);
         }
-        st_as<SNT>(reinterpret_cast<u32x2 *>(dst + e), w);
+        st_as<ADAM4_SNT>(reinterpret_cast<u32x2 *>(dst + e), w);
     }
+}
+
+// Sweep 2 without a decay mask.
+template <bool PACK>
+__global__ __launch_bounds__(PARO_ADAM4_TPB) void k_adam4(const AdamConsts a, const double *__restrict__ total_sumsq,
+                                                          const float *__restrict__ g, float *__restrict__ p,
+                                                          float *__restrict__ m, float *__restrict__ v,
+                                                          uint16_t *__restrict__ dst, int64_t n) {
+    if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
+    const float sc = scale_from_norm(a, total_sumsq);
+    const int64_t e = ((int64_t)blockIdx.x * PARO_ADAM4_TPB + threadIdx.x) * 4;      // n is a multiple of 8
+    if (e >= n) return;
+    const f32x4 G = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(g + e));
+    const State4 s = load_state4(p, m, v, e);
+    const float gg[4] = {G.x, G.y, G.z, G.w};
+    update4<PACK>(a, sc, gg, s, p, m, v, dst, e);
+}
+
+// Single sweep (no clipping), chunk layout, no decay mask: fold, Adam and pack.
+template <int DT>
+__global__ __launch_bounds__(PARO_FOLD4_TPB) void k_fused4(const SrcTable src, int P, int group_len, int64_t n,
+                                                           const AdamConsts a, float *__restrict__ p,
+                                                           float *__restrict__ m, float *__restrict__ v,
+                                                           uint16_t *__restrict__ dst) {
+    const int64_t e = ((int64_t)blockIdx.x * PARO_FOLD4_TPB + threadIdx.x) * 4;
+    if (e >= n) return;
+    const State4 s = load_state4(p, m, v, e);
+    Chunk4Loader<DT> ld{e};
+    float X[4];
+    fold8<Chunk4Loader<DT>, false>(ld, src, P, group_len, X);
+    update4<true>(a, a.grad_scale, X, s, p, m, v, dst, e);
 }
 
 // Single sweep when nothing has to wait for the norm: fold, Adam and pack; the
@@ -320,28 +353,33 @@ __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P,
     }
 }
 
-// Low-precision pack alone.
-__global__ __launch_bounds__(TPB) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n,
-                                              int pack_dtype) {
-    const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles) {
-        const int64_t e = tile * TILE + threadIdx.x * EPT;
-        if (e < n) {
-            float pp[8];
-            load8_f32(p + e, pp);
-            store8_lowp(dst + e, pp, pack_dtype);
-        }
+// Low-precision pack alone: one-wave blocks, 4 elements per thread.
+__global__ __launch_bounds__(64) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n,
+                                             int pack_dtype) {
+    const int64_t e = ((int64_t)blockIdx.x * 64 + threadIdx.x) * 4;          // n is a multiple of 8
+    if (e >= n) return;
+    const f32x4 P = ld_as<true>(reinterpret_cast<const f32x4 *>(p + e));
+    u32x2 w;
+    if (pack_dtype == PARO_F16) {
+        w.x = f32_to_f16_bits(P.x) | (f32_to_f16_bits(P.y) << 16);
+        w.y = f32_to_f16_bits(P.z) | (f32_to_f16_bits(P.w) << 16);
+    } else {
+        w.x = f32_to_bf16_rne(P.x) | (f32_to_bf16_rne(P.y) << 16);
+        w.y = f32_to_bf16_rne(P.z) | (f32_to_bf16_rne(P.w) << 16);
     }
+    st_as<true>(reinterpret_cast<u32x2 *>(dst + e), w);
 }
 
-// One ring hop / one accumulation: out = a + b, element by element in fp32.
+// One ring hop / one accumulation: out = a + b, element by element in fp32.  One-wave blocks,
+// 4 elements per thread, streaming loads and stores.
 template <int DT>
-__device__ __forceinline__ void hop_load8(const void *a, int64_t e, float x[8]) {
+__device__ __forceinline__ void hop_load4(const void *a, int64_t e, float x[4]) {
     if (DT != PARO_F32) {
-        const u32x4 q = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(a) + e));
-        unpack16x8<DT>(q, x);
+        const u32x2 q = ld_as<true>(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(a) + e));
+        x[0] = cvt_lo<DT>(q.x); x[1] = cvt_hi<DT>(q.x); x[2] = cvt_lo<DT>(q.y); x[3] = cvt_hi<DT>(q.y);
     } else {
-        load8_f32<false>(static_cast<const float *>(a) + e, x);
+        const f32x4 q = ld_as<true>(reinterpret_cast<const f32x4 *>(static_cast<const float *>(a) + e));
+        x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
     }
 }
 template <int DT>
@@ -350,24 +388,22 @@ __device__ __forceinline__ float hop_load1(const void *a, int64_t i) {
 }
 
 template <int DA, int DB>
-__global__ __launch_bounds__(TPB) void k_hop(const void *a, const void *b, float *out, int64_t n) {
-    const int64_t e = ((int64_t)blockIdx.x * TPB + threadIdx.x) * EPT;
-    if (e + EPT <= n) {
-        float x[8], y[8];
-        hop_load8<DA>(a, e, x);
-        hop_load8<DB>(b, e, y);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = x[i] + y[i];
-        store8_f32(out + e, x);
+__global__ __launch_bounds__(64) void k_hop(const void *a, const void *b, float *out, int64_t n) {
+    const int64_t e = ((int64_t)blockIdx.x * 64 + threadIdx.x) * 4;
+    if (e + 4 <= n) {
+        float x[4], y[4];
+        hop_load4<DA>(a, e, x);
+        hop_load4<DB>(b, e, y);
+        st_as<true>(reinterpret_cast<f32x4 *>(out + e), f32x4{x[0] + y[0], x[1] + y[1], x[2] + y[2], x[3] + y[3]});
     } else {
         for (int64_t i = e; i < n; ++i) out[i] = hop_load1<DA>(a, i) + hop_load1<DB>(b, i);   // last, partial group
     }
 }
 
 // Plain copy of n 16-byte units (an all-gather message landing in the parameter buffer).
-__global__ __launch_bounds__(TPB) void k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (i < n) dst[i] = ld_contrib(src + i);
+__global__ __launch_bounds__(64) void k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (i < n) st_as<true>(dst + i, ld_as<true>(src + i));
 }
 
 }  // namespace
@@ -396,6 +432,16 @@ int fold4_grid(int64_t n) {
     const int64_t per_block = 4 * (int64_t)PARO_FOLD4_TPB;
     const int64_t nb = (n + per_block - 1) / per_block;
     return (int)(nb < 1 ? 1 : nb);
+}
+
+// Occupancy throttle for the one-wave-block sweeps: on this part the mixed read/write sweeps run
+// faster with 12-14 waves per compute unit in flight than with the 32 the registers would allow
+// (fewer requests fighting over DRAM pages).  The launch asks for dynamic LDS it never touches,
+// sized so that only `waves_per_cu` blocks fit on a compute unit.
+unsigned throttle_lds(const paro_plan_t *pl, int waves_per_cu) {
+    if (waves_per_cu <= 0) return 0;
+    unsigned bytes = (unsigned)(pl->dev.lds_per_cu / waves_per_cu) / 256u * 256u;
+    return bytes > 65536u ? 65536u : bytes;
 }
 
 template <class T>
@@ -475,6 +521,8 @@ int ensure_device(paro_plan_t *pl) {
     paro_device_tables d;
     PARO_HIP(hipDeviceGetAttribute(&d.n_cu, hipDeviceAttributeMultiprocessorCount, dev));
     if (d.n_cu < 1) d.n_cu = 256;
+    PARO_HIP(hipDeviceGetAttribute(&d.lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev));
+    if (d.lds_per_cu < 65536) d.lds_per_cu = 65536;
     const int rc = fill_tables(pl, d);
     if (rc != PARO_OK) {
         free_tables(d);                    // nothing half-built stays behind
@@ -590,14 +638,15 @@ int launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int gr
     double *partials = pl->dev.partials;
     if (PARO_FOLD4 && layout == PARO_CHUNK) {
         const int grid = fold4_grid(n);
+        const unsigned lds = throttle_lds(pl, PARO_FOLD4_WAVES_PER_CU);
         if (pl->dtype[0] == PARO_BF16)
-            hipLaunchKernelGGL((k_reduce4<PARO_BF16, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), 0, st, tab, pl->P, group_len,
+            hipLaunchKernelGGL((k_reduce4<PARO_BF16, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len,
                                n, g, partials);
         else if (pl->dtype[0] == PARO_F16)
-            hipLaunchKernelGGL((k_reduce4<PARO_F16, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), 0, st, tab, pl->P, group_len,
+            hipLaunchKernelGGL((k_reduce4<PARO_F16, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len,
                                n, g, partials);
         else
-            hipLaunchKernelGGL((k_reduce4<PARO_F32, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), 0, st, tab, pl->P, group_len,
+            hipLaunchKernelGGL((k_reduce4<PARO_F32, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len,
                                n, g, partials);
         return grid;
     }
@@ -628,6 +677,20 @@ template <bool MASK>
 void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t flat_begin,
                   const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
+    if (PARO_FOLD4 && layout == PARO_CHUNK && !MASK) {
+        const int g4 = fold4_grid(n);
+        const unsigned lds = throttle_lds(pl, PARO_FUSED4_WAVES_PER_CU);
+        if (pl->dtype[0] == PARO_BF16)
+            hipLaunchKernelGGL((k_fused4<PARO_BF16>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len, n, a, p,
+                               m, v, dst);
+        else if (pl->dtype[0] == PARO_F16)
+            hipLaunchKernelGGL((k_fused4<PARO_F16>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len, n, a, p,
+                               m, v, dst);
+        else
+            hipLaunchKernelGGL((k_fused4<PARO_F32>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len, n, a, p,
+                               m, v, dst);
+        return;
+    }
     const int grid = grid_for(pl, n, PARO_TPBK_FOLD);
     TileSegs segs = segs_for(pl, flat_begin, true);
     if (layout == PARO_TENSORS) {
@@ -691,11 +754,12 @@ int do_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, c
     const bool mask = pl->any_no_decay;
     if (PARO_ADAM4 && !mask) {
         const int64_t nb = (on / 4 + PARO_ADAM4_TPB - 1) / PARO_ADAM4_TPB;
+        const unsigned lds = throttle_lds(pl, PARO_ADAM4_WAVES_PER_CU);
         if (dst)
-            hipLaunchKernelGGL((k_adam4<true>), dim3((unsigned)nb), dim3(PARO_ADAM4_TPB), 0, st, a, total_sumsq, grad, p, m,
+            hipLaunchKernelGGL((k_adam4<true>), dim3((unsigned)nb), dim3(PARO_ADAM4_TPB), lds, st, a, total_sumsq, grad, p, m,
                                v, dst, on);
         else
-            hipLaunchKernelGGL((k_adam4<false>), dim3((unsigned)nb), dim3(PARO_ADAM4_TPB), 0, st, a, total_sumsq, grad, p, m,
+            hipLaunchKernelGGL((k_adam4<false>), dim3((unsigned)nb), dim3(PARO_ADAM4_TPB), lds, st, a, total_sumsq, grad, p, m,
                                v, dst, on);
         PARO_HIP(hipGetLastError());
         return PARO_OK;
@@ -769,8 +833,9 @@ int paro_pack_params(paro_plan_t *pl, int rank, const float *p, uint16_t *dst_ba
     if ((rc = ensure_device(pl))) return rc;
     int64_t dl, so, sl;
     paro_pack_slot(pl, rank, &dl, &so, &sl);
-    hipLaunchKernelGGL(k_pack, dim3(grid_for(pl, sl, PARO_TPBK_ADAM)), dim3(TPB), 0, static_cast<hipStream_t>(stream), p,
-                       dst_base + so, sl, pl->pack_dtype);
+    const int64_t nb = (sl / 4 + 63) / 64;
+    hipLaunchKernelGGL(k_pack, dim3((unsigned)(nb < 1 ? 1 : nb)), dim3(64), throttle_lds(pl, PARO_COPY_WAVES_PER_CU),
+                       static_cast<hipStream_t>(stream), p, dst_base + so, sl, pl->pack_dtype);
     PARO_HIP(hipGetLastError());
     return PARO_OK;
 }
@@ -823,12 +888,14 @@ int paro_step_fused(paro_plan_t *pl, int rank, const void *const *contrib, int l
 
 // ---- ring hops and scheduled transfers ----------------------------------------
 namespace {
-int launch_hop(const void *a, int da, const void *b, int db, float *out, int64_t n, hipStream_t st) {
+int launch_hop(const paro_plan_t *pl, const void *a, int da, const void *b, int db, float *out, int64_t n,
+               hipStream_t st) {
     if (n <= 0) return PARO_OK;
-    const int64_t groups = (n + EPT - 1) / EPT;
-    const int grid = (int)((groups + TPB - 1) / TPB);
+    const int64_t groups = (n + 3) / 4;
+    const unsigned grid = (unsigned)((groups + 63) / 64);
+    const unsigned lds = throttle_lds(pl, PARO_HOP_WAVES_PER_CU);
 #define PARO_HOP_CASE(A, B)                                                                                   \
-    if (da == A && db == B) hipLaunchKernelGGL((k_hop<A, B>), dim3(grid), dim3(TPB), 0, st, a, b, out, n)
+    if (da == A && db == B) hipLaunchKernelGGL((k_hop<A, B>), dim3(grid), dim3(64), lds, st, a, b, out, n)
     PARO_HOP_CASE(PARO_BF16, PARO_BF16); PARO_HOP_CASE(PARO_BF16, PARO_F32); PARO_HOP_CASE(PARO_BF16, PARO_F16);
     PARO_HOP_CASE(PARO_F32, PARO_BF16);  PARO_HOP_CASE(PARO_F32, PARO_F32);  PARO_HOP_CASE(PARO_F32, PARO_F16);
     PARO_HOP_CASE(PARO_F16, PARO_BF16);  PARO_HOP_CASE(PARO_F16, PARO_F32);  PARO_HOP_CASE(PARO_F16, PARO_F16);
@@ -854,7 +921,7 @@ int paro_ring_hop(paro_plan_t *pl, const void *partial_in, int in_dtype, const v
         (local_dtype != PARO_F32 && static_cast<const void *>(out) == local))
         return fail(PARO_EINVAL, "paro_ring_hop: out may only alias an fp32 operand");
     if ((rc = ensure_device(pl))) return rc;
-    return launch_hop(partial_in, in_dtype, local, local_dtype, out, n, static_cast<hipStream_t>(stream));
+    return launch_hop(pl, partial_in, in_dtype, local, local_dtype, out, n, static_cast<hipStream_t>(stream));
 }
 
 int64_t paro_collective_step(paro_plan_t *pl, int rank, int sched, int collective, int phase, int ring, int step,
@@ -881,15 +948,15 @@ int64_t paro_collective_step(paro_plan_t *pl, int rank, int sched, int collectiv
         if (collective == PARO_RS) {
             const float *from = static_cast<const float *>(bufs[m.recv_from]) + m.recv_off;
             float *mine = static_cast<float *>(bufs[rank]) + m.recv_off;
-            if ((rc = launch_hop(from, PARO_F32, mine, PARO_F32, mine, m.recv_len, st))) return rc;
+            if ((rc = launch_hop(pl, from, PARO_F32, mine, PARO_F32, mine, m.recv_len, st))) return rc;
         } else {
             const uint16_t *from = static_cast<const uint16_t *>(bufs[m.recv_from]) + m.recv_off;
             uint16_t *mine = static_cast<uint16_t *>(bufs[rank]) + m.recv_off;
             const int64_t n16 = m.recv_len / 8;             // ranges are whole chunks: multiples of 8 elements
-            const int grid = (int)((n16 + TPB - 1) / TPB);
+            const unsigned grid = (unsigned)((n16 + 63) / 64);
             if (n16 > 0) {
-                hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(TPB), 0, st, reinterpret_cast<const u32x4 *>(from),
-                                   reinterpret_cast<u32x4 *>(mine), n16);
+                hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(64), throttle_lds(pl, PARO_COPY_WAVES_PER_CU), st,
+                                   reinterpret_cast<const u32x4 *>(from), reinterpret_cast<u32x4 *>(mine), n16);
                 PARO_HIP(hipGetLastError());
             }
         }

@@ -21,6 +21,7 @@ struct paro_tile_info {
 struct paro_device_tables {
     int device = -1;
     int n_cu = 0;
+    int lds_per_cu = 0;             // bytes of LDS a compute unit has (for the occupancy throttle)
     int64_t *nz_off = nullptr;      // [n_nz + 1] flat start of every non-empty tensor, then Psi
     int32_t *nz_tensor = nullptr;   // [n_nz]     index of that tensor in the caller's list
     uint8_t *dtype = nullptr;       // [T]
