@@ -76,20 +76,19 @@ __device__ __forceinline__ void adam1(const AdamConsts &a, float sc, bool decays
     }
 }
 
-// Which tiles a block takes: TPBK == 0: grid-stride (persistent blocks); TPBK > 0: a run of
-// TPBK consecutive tiles.
-#define TILE_LOOP(TPBK, tile, ntiles)                                                                       \
-    for (int64_t tile = (TPBK) ? (int64_t)blockIdx.x * (TPBK) : (int64_t)blockIdx.x,                        \
-                 tile##_end = (TPBK) ? min((int64_t)(ntiles), tile + (TPBK)) : (int64_t)(ntiles),           \
-                 tile##_step = (TPBK) ? 1 : (int64_t)gridDim.x;                                             \
-         tile < tile##_end; tile += tile##_step)
+// Which tiles a block takes: a run of TPBK consecutive tiles of the launch's range, or, when the
+// launch comes with a list of tiles, a run of TPBK entries of that list.
+#define TILE_LOOP(TPBK, tile, ntiles, list, n_list)                                                          \
+    for (int64_t it_ = (int64_t)blockIdx.x * (TPBK),                                                         \
+                 it_end_ = min((list) ? (int64_t)(n_list) : (int64_t)(ntiles), it_ + (TPBK)), tile = 0;      \
+         it_ < it_end_ && ((tile = (list) ? (int64_t)(list)[it_] : it_), true); ++it_)
 
 // --------------------------------------------------------------------- kernels
 // Sweep 1: g = fold of the contributions; optional per-block partial of sum g^2.
 template <class Ld, bool SUMSQ>
 __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P, int group_len, int64_t n,
                                                 float *__restrict__ g, double *__restrict__ partials,
-                                                TileSegs segs) {
+                                                TileSegs segs, const int32_t *__restrict__ tile_list, int n_list) {
     __shared__ int64_t s_off[Ld::kTensor ? TILE + 2 : 1];
     __shared__ int s_head[2];
     __shared__ uintptr_t s_ptr[Ld::kTensor ? PARO_MAX_RANKS : 1];
@@ -97,7 +96,7 @@ __global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P
     segs.s_head = s_head;
     double acc = 0.0;
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles) {
+    TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles, tile_list, n_list) {
         if (Ld::kTensor) {
             segs.begin_tile(tile * TILE);
             ld.begin_tile(segs, src, P, s_ptr);
@@ -189,7 +188,8 @@ template <bool PACK, bool MASK>
 __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *__restrict__ total_sumsq,
                                               const float *__restrict__ g, float *__restrict__ p,
                                               float *__restrict__ m, float *__restrict__ v,
-                                              uint16_t *__restrict__ dst, int64_t n, TileSegs segs) {
+                                              uint16_t *__restrict__ dst, int64_t n, TileSegs segs,
+                                              const int32_t *__restrict__ tile_list, int n_list) {
     __shared__ int64_t s_off[MASK ? TILE + 2 : 1];
     __shared__ int s_head[2];
     segs.s_off = s_off;
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *
     if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
     const float sc = scale_from_norm(a, total_sumsq);
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles) {
+    TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles, tile_list, n_list) {
         if (MASK) segs.begin_tile(tile * TILE);
         const int rel0 = threadIdx.x * EPT;
         const int64_t e = tile * TILE + rel0;
@@ -246,12 +246,12 @@ __device__ __forceinline__ State4 load_state4(const float *p, const float *m, co
 
 // Adam on the thread's 4 elements, state and (optionally) the low-precision copy written back.
 template <bool PACK>
-__device__ __forceinline__ void update4(const AdamConsts &a, float sc, const float gg[4], const State4 &s, float *p,
-                                        float *m, float *v, uint16_t *dst, int64_t e) {
+__device__ __forceinline__ void update4(const AdamConsts &a, float sc, bool decays, const float gg[4], const State4 &s,
+                                        float *p, float *m, float *v, uint16_t *dst, int64_t e) {
     float pp[4] = {s.p.x, s.p.y, s.p.z, s.p.w}, mm[4] = {s.m.x, s.m.y, s.m.z, s.m.w},
           vv[4] = {s.v.x, s.v.y, s.v.z, s.v.w};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) adam1(a, sc, true, gg[i], pp[i], mm[i], vv[i]);
+    for (int i = 0; i < 4; ++i) adam1(a, sc, decays, gg[i], pp[i], mm[i], vv[i]);
     st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(p + e), f32x4{pp[0], pp[1], pp[2], pp[3]});
     st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(m + e), f32x4{mm[0], mm[1], mm[2], mm[3]});
     st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(v + e), f32x4{vv[0], vv[1], vv[2], vv[3]});
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(PARO_ADAM4_TPB) void k_adam4(const AdamConsts a, co
     const f32x4 G = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(g + e));
     const State4 s = load_state4(p, m, v, e);
     const float gg[4] = {G.x, G.y, G.z, G.w};
-    update4<PACK>(a, sc, gg, s, p, m, v, dst, e);
+    update4<PACK>(a, sc, true, gg, s, p, m, v, dst, e);
 }
 
 // Single sweep (no clipping), chunk layout, no decay mask: fold, Adam and pack.
@@ -296,7 +296,157 @@ __global__ __launch_bounds__(PARO_FOLD4_TPB) void k_fused4(const SrcTable src, i
     Chunk4Loader<DT> ld{e};
     float X[4];
     fold8<Chunk4Loader<DT>, false>(ld, src, P, group_len, X);
-    update4<true>(a, a.grad_scale, X, s, p, m, v, dst, e);
+    update4<true>(a, a.grad_scale, true, X, s, p, m, v, dst, e);
+}
+
+// ---- the one-wave shape for work that depends on the tensor an element belongs to (tensor
+// layout, weight-decay mask).  The plan's per-tile table says, for every 2048-element tile of a
+// chunk, whether it lies inside one tensor (then the 8 one-wave blocks of the tile know their
+// tensor and offset without any search), is all padding, or holds a tensor boundary.  Boundary
+// tiles are left to the tile-at-a-time kernels, which then run over the plan's list of such
+// tiles only; the blocks here return at once for them.
+struct Piece {
+    int tensor;        // >= 0: the block's 256 elements lie in this tensor; -1: boundary tile; -2: padding
+    int dt;            // the tensor's gradient dtype
+    int64_t toff;      // offset of the block's first element inside the tensor
+};
+
+__device__ __forceinline__ Piece piece_of(const paro_tile_info *__restrict__ tile_tab, int64_t e0) {
+    const paro_tile_info info = tile_tab[e0 / TILE];           // one address for the whole wave
+    Piece pc;
+    pc.tensor = __builtin_amdgcn_readfirstlane(info.tensor);  // tell the compiler: wave-uniform
+    pc.dt = __builtin_amdgcn_readfirstlane(info.first_seg);
+    const int64_t toff = info.toff + (e0 % TILE);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)toff);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uint64_t)toff >> 32));
+    pc.toff = (int64_t)(((uint64_t)hi << 32) | lo);
+    return pc;
+}
+
+// 4 elements per thread out of one tensor's per-rank gradients.  ALIGNED: every rank's first byte
+// for this block is 8-byte (2-byte dtypes) or 16-byte (fp32) aligned, so one vector load fetches
+// the thread's 4 values; otherwise element loads.
+template <int DT, bool ALIGNED>
+struct Tensor4Loader {
+    static constexpr bool kTensor = false;
+    static constexpr int kElems = 4;
+    static constexpr int kBatch = PARO_BATCH_BF16;
+    using Raw = std::conditional_t<DT == PARO_F32, u32x4, u32x2>;
+    int tensor;
+    int64_t byte_off;          // of the thread's first element inside the tensor
+    template <bool SLOW>
+    __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
+        const uintptr_t base = static_cast<const uintptr_t *>(src.p[k])[tensor] + (uintptr_t)byte_off;
+        if constexpr (ALIGNED) {
+            r = ld_contrib(global_ptr<Raw>(base));
+        } else if constexpr (DT != PARO_F32) {
+            const auto *h = global_ptr<uint16_t>(base);
+            r.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
+            r.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
+        } else {
+            const auto *w = global_ptr<unsigned int>(base);
+            r = u32x4{w[0], w[1], w[2], w[3]};
+        }
+    }
+    template <bool SLOW>
+    __device__ __forceinline__ void unpack(const SrcTable &s, int k, const Raw &r, float x[4]) const {
+        Chunk4Loader<DT>{0}.template unpack<SLOW>(s, k, r, x);
+    }
+};
+
+template <int DT>
+__device__ __forceinline__ void fold_piece_dt(const Piece &pc, const SrcTable &src, int P, int group_len, float X[4]) {
+    constexpr int ESIZE = DT == PARO_F32 ? 4 : 2;
+    constexpr uintptr_t NEED = DT == PARO_F32 ? 15 : 7;
+    bool aligned = true;                                         // wave-uniform
+    for (int k = 0; k < P; ++k) {
+        const uintptr_t b = static_cast<const uintptr_t *>(src.p[k])[pc.tensor];
+        aligned = aligned && ((b + (uintptr_t)pc.toff * ESIZE) & NEED) == 0;
+    }
+    const int64_t byte_off = (pc.toff + (int64_t)threadIdx.x * 4) * ESIZE;
+    if (aligned) {
+        Tensor4Loader<DT, true> ld{pc.tensor, byte_off};
+        fold8<Tensor4Loader<DT, true>, false>(ld, src, P, group_len, X);
+    } else {
+        Tensor4Loader<DT, false> ld{pc.tensor, byte_off};
+        fold8<Tensor4Loader<DT, false>, false>(ld, src, P, group_len, X);
+    }
+}
+
+// The ordered fold for a block whose elements lie in one tensor (pc.tensor >= 0).
+__device__ __forceinline__ void fold_piece(const Piece &pc, const SrcTable &src, int P, int group_len, float X[4]) {
+    if (pc.dt == PARO_BF16) fold_piece_dt<PARO_BF16>(pc, src, P, group_len, X);
+    else if (pc.dt == PARO_F16) fold_piece_dt<PARO_F16>(pc, src, P, group_len, X);
+    else fold_piece_dt<PARO_F32>(pc, src, P, group_len, X);
+}
+
+// Sweep 1, tensor layout, tiles that lie in one tensor or in the padding.  Every block writes its
+// partial sum (0 for a block that leaves its tile to the boundary-tile launch).
+template <bool SUMSQ>
+__global__ __launch_bounds__(64) void k_reduce4t(const SrcTable src, int P, int group_len, int64_t n,
+                                                 float *__restrict__ g, double *__restrict__ partials,
+                                                 const paro_tile_info *__restrict__ tile_tab) {
+    const int64_t e0 = (int64_t)blockIdx.x * 256, e = e0 + (int64_t)threadIdx.x * 4;
+    const Piece pc = piece_of(tile_tab, e0);
+    double acc = 0.0;
+    if (pc.tensor != -1 && e < n) {
+        float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};                   // padding: the sum of zeros
+        if (pc.tensor >= 0) fold_piece(pc, src, P, group_len, X);
+        st_as<PARO_NT_GSTORE != 0>(reinterpret_cast<f32x4 *>(g + e), f32x4{X[0], X[1], X[2], X[3]});
+        if (SUMSQ) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc += (double)X[i] * (double)X[i];
+        }
+    }
+    if (SUMSQ) {
+        const double s = block_sum<64>(acc);
+        if (threadIdx.x == 0) partials[blockIdx.x] = s;
+    }
+}
+
+// Sweep 2 with a weight-decay mask, same tiles.
+template <bool PACK>
+__global__ __launch_bounds__(64) void k_adam4m(const AdamConsts a, const double *__restrict__ total_sumsq,
+                                               const float *__restrict__ g, float *__restrict__ p,
+                                               float *__restrict__ m, float *__restrict__ v,
+                                               uint16_t *__restrict__ dst, int64_t n,
+                                               const paro_tile_info *__restrict__ tile_tab,
+                                               const uint8_t *__restrict__ no_decay) {
+    if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
+    const float sc = scale_from_norm(a, total_sumsq);
+    const int64_t e0 = (int64_t)blockIdx.x * 256, e = e0 + (int64_t)threadIdx.x * 4;
+    if (e >= n) return;
+    const Piece pc = piece_of(tile_tab, e0);
+    if (pc.tensor == -1) return;
+    const bool decays = pc.tensor < 0 || no_decay[pc.tensor] == 0;      // padding decays (and stays 0)
+    const f32x4 G = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(g + e));
+    const State4 s = load_state4(p, m, v, e);
+    const float gg[4] = {G.x, G.y, G.z, G.w};
+    update4<PACK>(a, sc, decays, gg, s, p, m, v, dst, e);
+}
+
+// Single sweep (no clipping) for the tensor layout and / or a weight-decay mask, same tiles.
+// TENSORS: contributions are per-tensor gradients; else arrays in shard coordinates of dtype DT.
+template <bool TENSORS, int DT, bool MASK>
+__global__ __launch_bounds__(64) void k_fused4t(const SrcTable src, int P, int group_len, int64_t n, const AdamConsts a,
+                                                float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
+                                                uint16_t *__restrict__ dst,
+                                                const paro_tile_info *__restrict__ tile_tab,
+                                                const uint8_t *__restrict__ no_decay) {
+    const int64_t e0 = (int64_t)blockIdx.x * 256, e = e0 + (int64_t)threadIdx.x * 4;
+    if (e >= n) return;
+    const Piece pc = piece_of(tile_tab, e0);
+    if (pc.tensor == -1) return;
+    const bool decays = !MASK || pc.tensor < 0 || no_decay[pc.tensor] == 0;
+    const State4 s = load_state4(p, m, v, e);
+    float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if constexpr (TENSORS) {
+        if (pc.tensor >= 0) fold_piece(pc, src, P, group_len, X);
+    } else {
+        Chunk4Loader<DT> ld{e};
+        fold8<Chunk4Loader<DT>, false>(ld, src, P, group_len, X);
+    }
+    update4<true>(a, a.grad_scale, decays, X, s, p, m, v, dst, e);
 }
 
 // Single sweep when nothing has to wait for the norm: fold, Adam and pack; the
@@ -304,7 +454,8 @@ __global__ __launch_bounds__(PARO_FOLD4_TPB) void k_fused4(const SrcTable src, i
 template <class Ld, bool MASK>
 __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P, int group_len, int64_t n,
                                                const AdamConsts a, float *__restrict__ p, float *__restrict__ m,
-                                               float *__restrict__ v, uint16_t *__restrict__ dst, TileSegs segs) {
+                                               float *__restrict__ v, uint16_t *__restrict__ dst, TileSegs segs,
+                                               const int32_t *__restrict__ tile_list, int n_list) {
     constexpr bool NEED_SEGS = Ld::kTensor || MASK;
     __shared__ int64_t s_off[NEED_SEGS ? TILE + 2 : 1];
     __shared__ int s_head[2];
@@ -313,7 +464,7 @@ __global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P,
     segs.s_head = s_head;
     const float sc = a.grad_scale;                     // no clipping on this path
     const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles) {
+    TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles, tile_list, n_list) {
         if (NEED_SEGS) segs.begin_tile(tile * TILE);
         if (Ld::kTensor) ld.begin_tile(segs, src, P, s_ptr);
         const int rel0 = threadIdx.x * EPT;
@@ -458,6 +609,7 @@ void free_tables(paro_device_tables &d) {
     (void)hipFree(d.dtype);
     (void)hipFree(d.no_decay);
     (void)hipFree(d.tile_tab);
+    (void)hipFree(d.slow_tiles);
     (void)hipFree(d.partials);
     d = paro_device_tables();
 }
@@ -468,39 +620,11 @@ int fill_tables(const paro_plan_t *pl, paro_device_tables &d) {
     if ((rc = upload(&d.nz_tensor, pl->nz_tensor.data(), pl->nz_tensor.size()))) return rc;
     if ((rc = upload(&d.dtype, pl->dtype.data(), pl->dtype.size()))) return rc;
     if ((rc = upload(&d.no_decay, pl->no_decay.data(), pl->no_decay.size()))) return rc;
-    // per-tile summaries for chunk-aligned launches over the tensor layout (16 B per 2048 elements)
     d.tiles_per_chunk = (pl->L + TILE - 1) / TILE;
-    if (pl->T > 1 && (int64_t)pl->P * d.tiles_per_chunk <= (int64_t)4 << 20) {
-        std::vector<paro_tile_info> tab;
-        try {
-            tab.resize((size_t)pl->P * d.tiles_per_chunk);
-        } catch (const std::bad_alloc &) {
-            return fail(PARO_ENOMEM, "out of host memory while building the per-tile table");
-        }
-        const int64_t n_nz = (int64_t)pl->nz_tensor.size();
-        for (int c = 0; c < pl->P; ++c) {
-            for (int64_t i = 0; i < d.tiles_per_chunk; ++i) {
-                const int64_t f0 = (int64_t)c * pl->L + i * TILE;
-                const int64_t f1 = std::min(f0 + (int64_t)TILE, (int64_t)(c + 1) * pl->L);   // end of the tile
-                paro_tile_info &ti = tab[(size_t)c * d.tiles_per_chunk + i];
-                ti.toff = 0;
-                ti.tensor = -1;
-                ti.first_seg = (int32_t)n_nz;
-                if (f0 >= pl->total) continue;
-                const int64_t k = std::upper_bound(pl->nz_off.begin(), pl->nz_off.end(), f0) - pl->nz_off.begin() - 1;
-                ti.first_seg = (int32_t)k;
-                if (f1 <= pl->nz_off[k + 1]) {
-                    ti.tensor = pl->nz_tensor[k];
-                    ti.toff = f0 - pl->nz_off[k];
-                    ti.first_seg = pl->dtype[ti.tensor];          // single-tensor tiles: the field carries the dtype
-                }
-            }
-        }
-        if ((rc = upload(&d.tile_tab, tab.data(), tab.size()))) return rc;
-    }
     // one partial per block of the largest sweep-1 launch (a launch covers one chunk of L elements),
     // followed by room for the second-level sums
-    int64_t n_part = std::max<int64_t>((pl->L + TILE - 1) / TILE, fold4_grid(pl->L));
+    // (the one-wave fold's blocks, then the blocks of a launch over the boundary tiles)
+    int64_t n_part = fold4_grid(pl->L) + (pl->L + TILE - 1) / TILE;
     if (n_part < PARO_MAX_PARTIALS) n_part = PARO_MAX_PARTIALS;
     d.n_partials = n_part;
     const int64_t n_level2 = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
@@ -533,16 +657,77 @@ int ensure_device(paro_plan_t *pl) {
     return PARO_OK;
 }
 
-// Blocks of a launch over n elements, for a kernel that takes tpbk tiles per block (0 = persistent).
-int grid_for(const paro_plan_t *pl, int64_t n, int tpbk) {
-    const int64_t ntiles = (n + TILE - 1) / TILE;
-    if (tpbk > 0) {
-        const int64_t nb = (ntiles + tpbk - 1) / tpbk;
-        return (int)(nb < 1 ? 1 : nb);
+// Builds, once, the per-tile table and the per-chunk lists of boundary tiles (for calls that work
+// tensor by tensor: the tensor layout, a weight-decay mask).  Too large a table (more than 4 Mi
+// tiles) is not built; the callers then use the kernels that search.
+int ensure_tile_table(paro_plan_t *pl) {
+    std::lock_guard<std::mutex> lock(pl->dev_mutex);
+    paro_device_tables &d = pl->dev;
+    if (d.tile_tab_tried) return PARO_OK;
+    d.tile_tab_tried = true;
+    if ((int64_t)pl->P * d.tiles_per_chunk > (int64_t)4 << 20) return PARO_OK;
+    std::vector<paro_tile_info> tab;
+    std::vector<int32_t> slow;
+    try {
+        tab.resize((size_t)pl->P * d.tiles_per_chunk);
+        d.slow_start.assign((size_t)pl->P + 1, 0);
+        const int64_t n_nz = (int64_t)pl->nz_tensor.size();
+        for (int c = 0; c < pl->P; ++c) {
+            d.slow_start[c] = (int64_t)slow.size();
+            for (int64_t i = 0; i < d.tiles_per_chunk; ++i) {
+                const int64_t f0 = (int64_t)c * pl->L + i * TILE;
+                const int64_t f1 = std::min(f0 + (int64_t)TILE, (int64_t)(c + 1) * pl->L);   // end of the tile
+                paro_tile_info &ti = tab[(size_t)c * d.tiles_per_chunk + i];
+                ti.toff = 0;
+                ti.tensor = -2;
+                ti.first_seg = (int32_t)n_nz;
+                if (f0 >= pl->total) continue;
+                const int64_t k = std::upper_bound(pl->nz_off.begin(), pl->nz_off.end(), f0) - pl->nz_off.begin() - 1;
+                if (f1 <= pl->nz_off[k + 1]) {
+                    ti.tensor = pl->nz_tensor[k];
+                    ti.toff = f0 - pl->nz_off[k];
+                    ti.first_seg = pl->dtype[ti.tensor];
+                } else {
+                    ti.tensor = -1;
+                    ti.first_seg = (int32_t)k;
+                    slow.push_back((int32_t)i);
+                }
+            }
+        }
+        d.slow_start[pl->P] = (int64_t)slow.size();
+    } catch (const std::bad_alloc &) {
+        return fail(PARO_ENOMEM, "out of host memory while building the per-tile table");
     }
-    int64_t cap = (int64_t)pl->dev.n_cu * BLOCKS_PER_CU;
-    if (cap > PARO_MAX_PARTIALS) cap = PARO_MAX_PARTIALS;
-    return (int)(ntiles < cap ? (ntiles < 1 ? 1 : ntiles) : cap);
+    int rc;
+    if ((rc = upload(&d.slow_tiles, slow.data(), slow.size()))) return rc;
+    if ((rc = upload(&d.tile_tab, tab.data(), tab.size()))) {
+        (void)hipFree(d.slow_tiles);
+        d.slow_tiles = nullptr;
+        return rc;
+    }
+    return PARO_OK;
+}
+
+// Blocks of a launch over n_tiles tiles, for a kernel that takes tpbk tiles per block.
+int grid_for_tiles(int64_t n_tiles, int tpbk) {
+    const int64_t nb = (n_tiles + tpbk - 1) / tpbk;
+    return (int)(nb < 1 ? 1 : nb);
+}
+int grid_for(int64_t n, int tpbk) { return grid_for_tiles((n + TILE - 1) / TILE, tpbk); }
+
+// Chunk c's part of the per-tile table and of the list of boundary tiles (null / 0 without a table).
+struct ChunkTiles {
+    const paro_tile_info *tab = nullptr;
+    const int32_t *slow = nullptr;
+    int n_slow = 0;
+};
+ChunkTiles chunk_tiles(const paro_plan_t *pl, int64_t c) {
+    ChunkTiles ct;
+    if (!pl->dev.tile_tab) return ct;
+    ct.tab = pl->dev.tile_tab + c * pl->dev.tiles_per_chunk;
+    ct.slow = pl->dev.slow_tiles + pl->dev.slow_start[(size_t)c];
+    ct.n_slow = (int)(pl->dev.slow_start[(size_t)c + 1] - pl->dev.slow_start[(size_t)c]);
+    return ct;
 }
 
 TileSegs segs_for(const paro_plan_t *pl, int64_t range_begin, bool chunk_launch) {
@@ -630,87 +815,89 @@ void src_table(const paro_plan_t *pl, int chunk, const void *const *contrib, int
     *group_len = gl;
 }
 
-// Launches sweep 1 over one chunk; returns the number of per-block partial sums it writes.
+#define PARO_BY_DTYPE(dt, CALL)            \
+    do {                                   \
+        if ((dt) == PARO_BF16) {           \
+            constexpr int DT = PARO_BF16;  \
+            CALL;                          \
+        } else if ((dt) == PARO_F16) {     \
+            constexpr int DT = PARO_F16;   \
+            CALL;                          \
+        } else {                           \
+            constexpr int DT = PARO_F32;   \
+            CALL;                          \
+        }                                  \
+    } while (0)
+
+// Launches sweep 1 over chunk c; returns the number of per-block partial sums it writes.
 template <bool SUMSQ>
-int launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t flat_begin, float *g,
+int launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t c, float *g,
                   hipStream_t st) {
     const int64_t n = pl->L;
     double *partials = pl->dev.partials;
-    if (PARO_FOLD4 && layout == PARO_CHUNK) {
-        const int grid = fold4_grid(n);
-        const unsigned lds = throttle_lds(pl, PARO_FOLD4_WAVES_PER_CU);
-        if (pl->dtype[0] == PARO_BF16)
-            hipLaunchKernelGGL((k_reduce4<PARO_BF16, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len,
-                               n, g, partials);
-        else if (pl->dtype[0] == PARO_F16)
-            hipLaunchKernelGGL((k_reduce4<PARO_F16, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len,
-                               n, g, partials);
-        else
-            hipLaunchKernelGGL((k_reduce4<PARO_F32, SUMSQ>), dim3(grid), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len,
-                               n, g, partials);
+    const int g4 = fold4_grid(n);
+    const unsigned lds = throttle_lds(pl, PARO_FOLD4_WAVES_PER_CU);
+    if (layout == PARO_CHUNK) {
+        PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_reduce4<DT, SUMSQ>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab,
+                                                       pl->P, group_len, n, g, partials));
+        return g4;
+    }
+    TensorLoader ld;
+    ld.dtype = pl->dev.dtype;
+    TileSegs segs = segs_for(pl, c * pl->L, true);
+    const ChunkTiles ct = chunk_tiles(pl, c);
+    if (!ct.tab) {                        // no per-tile table: the searching kernel over every tile
+        const int grid = grid_for(n, PARO_TPBK_FOLD);
+        hipLaunchKernelGGL((k_reduce<TensorLoader, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, g,
+                           partials, segs, nullptr, 0);
         return grid;
     }
-    const int grid = grid_for(pl, n, PARO_TPBK_FOLD);
-    TileSegs segs = segs_for(pl, flat_begin, true);
-    if (layout == PARO_TENSORS) {
-        TensorLoader ld;
-        ld.dtype = pl->dev.dtype;
-        hipLaunchKernelGGL((k_reduce<TensorLoader, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, g,
-                           partials, segs);
-    } else if (pl->dtype[0] == PARO_BF16) {
-        ChunkLoader<PARO_BF16> ld{0};
-        hipLaunchKernelGGL((k_reduce<ChunkLoader<PARO_BF16>, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
-                           group_len, n, g, partials, segs);
-    } else if (pl->dtype[0] == PARO_F16) {
-        ChunkLoader<PARO_F16> ld{0};
-        hipLaunchKernelGGL((k_reduce<ChunkLoader<PARO_F16>, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
-                           group_len, n, g, partials, segs);
-    } else {
-        ChunkLoader<PARO_F32> ld{0};
-        hipLaunchKernelGGL((k_reduce<ChunkLoader<PARO_F32>, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
-                           group_len, n, g, partials, segs);
-    }
-    return grid;
+    hipLaunchKernelGGL((k_reduce4t<SUMSQ>), dim3(g4), dim3(64), lds, st, tab, pl->P, group_len, n, g, partials, ct.tab);
+    if (ct.n_slow == 0) return g4;
+    const int grid = grid_for_tiles(ct.n_slow, PARO_TPBK_FOLD);
+    hipLaunchKernelGGL((k_reduce<TensorLoader, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, g,
+                       partials + g4, segs, ct.slow, ct.n_slow);
+    return g4 + grid;
 }
 
+// Launches the single sweep (no clipping) over chunk c.
 template <bool MASK>
-void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t flat_begin,
-                  const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
+void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t c, const AdamConsts &a,
+                  float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
-    if (PARO_FOLD4 && layout == PARO_CHUNK && !MASK) {
-        const int g4 = fold4_grid(n);
-        const unsigned lds = throttle_lds(pl, PARO_FUSED4_WAVES_PER_CU);
-        if (pl->dtype[0] == PARO_BF16)
-            hipLaunchKernelGGL((k_fused4<PARO_BF16>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len, n, a, p,
-                               m, v, dst);
-        else if (pl->dtype[0] == PARO_F16)
-            hipLaunchKernelGGL((k_fused4<PARO_F16>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len, n, a, p,
-                               m, v, dst);
-        else
-            hipLaunchKernelGGL((k_fused4<PARO_F32>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P, group_len, n, a, p,
-                               m, v, dst);
+    const int g4 = fold4_grid(n);
+    const unsigned lds = throttle_lds(pl, PARO_FUSED4_WAVES_PER_CU);
+    if (layout == PARO_CHUNK && !MASK) {
+        PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_fused4<DT>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P,
+                                                       group_len, n, a, p, m, v, dst));
         return;
     }
-    const int grid = grid_for(pl, n, PARO_TPBK_FOLD);
-    TileSegs segs = segs_for(pl, flat_begin, true);
+    TileSegs segs = segs_for(pl, c * pl->L, true);
+    const ChunkTiles ct = chunk_tiles(pl, c);
+    // the tile-at-a-time kernel: over every tile without a table, else over the boundary tiles
+    const int n_list = ct.tab ? ct.n_slow : 0;
+    const int grid = ct.tab ? grid_for_tiles(ct.n_slow, PARO_TPBK_FOLD) : grid_for(n, PARO_TPBK_FOLD);
+    const uint8_t *no_decay = pl->dev.no_decay;
     if (layout == PARO_TENSORS) {
+        if (ct.tab)
+            hipLaunchKernelGGL((k_fused4t<true, PARO_BF16, MASK>), dim3(g4), dim3(64), lds, st, tab, pl->P, group_len, n, a, p,
+                               m, v, dst, ct.tab, no_decay);
+        if (ct.tab && n_list == 0) return;
         TensorLoader ld;
         ld.dtype = pl->dev.dtype;
         hipLaunchKernelGGL((k_fused<TensorLoader, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, a,
-                           p, m, v, dst, segs);
-    } else if (pl->dtype[0] == PARO_BF16) {
-        ChunkLoader<PARO_BF16> ld{0};
-        hipLaunchKernelGGL((k_fused<ChunkLoader<PARO_BF16>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
-                           group_len, n, a, p, m, v, dst, segs);
-    } else if (pl->dtype[0] == PARO_F16) {
-        ChunkLoader<PARO_F16> ld{0};
-        hipLaunchKernelGGL((k_fused<ChunkLoader<PARO_F16>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
-                           group_len, n, a, p, m, v, dst, segs);
-    } else {
-        ChunkLoader<PARO_F32> ld{0};
-        hipLaunchKernelGGL((k_fused<ChunkLoader<PARO_F32>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P,
-                           group_len, n, a, p, m, v, dst, segs);
+                           p, m, v, dst, segs, ct.slow, n_list);
+        return;
     }
+    if (ct.tab)
+        PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_fused4t<false, DT, MASK>), dim3(g4), dim3(64), lds, st, tab, pl->P,
+                                                       group_len, n, a, p, m, v, dst, ct.tab, no_decay));
+    if (ct.tab && n_list == 0) return;
+    PARO_BY_DTYPE(pl->dtype[0], {
+        ChunkLoader<DT> ld{0};
+        hipLaunchKernelGGL((k_fused<ChunkLoader<DT>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, a, p,
+                           m, v, dst, segs, ct.slow, n_list);
+    });
 }
 
 // Sweep 1 over the whole update range, chunk by chunk; the sum of squares covers
@@ -720,16 +907,16 @@ int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout,
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
     const int own = paro::chunk_of_rank(pl, rank);
-    int n_part = 0;                      // partial sums written by the launch over the rank's own chunk
+    int n_part = 0;                      // partial sums written by the launches over the rank's own chunk
     for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {
         SrcTable tab;
         int gl;
         const int64_t lo = c * pl->L - ob;
         src_table(pl, (int)c, contrib, layout, lo, &tab, &gl);
         if (c == own && sumsq_out)
-            n_part = launch_reduce<true>(pl, layout, tab, gl, c * pl->L, grad_out + lo, st);
+            n_part = launch_reduce<true>(pl, layout, tab, gl, c, grad_out + lo, st);
         else
-            launch_reduce<false>(pl, layout, tab, gl, c * pl->L, grad_out + lo, st);
+            launch_reduce<false>(pl, layout, tab, gl, c, grad_out + lo, st);
         PARO_HIP(hipGetLastError());
     }
     if (sumsq_out) {
@@ -747,35 +934,45 @@ int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout,
     return PARO_OK;
 }
 
-int do_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, const double *total_sumsq, float *p,
-            float *m, float *v, uint16_t *dst /* nullable: no pack */, hipStream_t st) {
+template <bool PACK>
+int launch_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, const double *total_sumsq, float *p,
+                float *m, float *v, uint16_t *dst, hipStream_t st) {
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
-    const bool mask = pl->any_no_decay;
-    if (PARO_ADAM4 && !mask) {
+    const unsigned lds = throttle_lds(pl, PARO_ADAM4_WAVES_PER_CU);
+    if (!pl->any_no_decay) {
         const int64_t nb = (on / 4 + PARO_ADAM4_TPB - 1) / PARO_ADAM4_TPB;
-        const unsigned lds = throttle_lds(pl, PARO_ADAM4_WAVES_PER_CU);
-        if (dst)
-            hipLaunchKernelGGL((k_adam4<true>), dim3((unsigned)nb), dim3(PARO_ADAM4_TPB), lds, st, a, total_sumsq, grad, p, m,
-                               v, dst, on);
-        else
-            hipLaunchKernelGGL((k_adam4<false>), dim3((unsigned)nb), dim3(PARO_ADAM4_TPB), lds, st, a, total_sumsq, grad, p, m,
-                               v, dst, on);
+        hipLaunchKernelGGL((k_adam4<PACK>), dim3((unsigned)nb), dim3(PARO_ADAM4_TPB), lds, st, a, total_sumsq, grad, p, m, v,
+                           dst, on);
         PARO_HIP(hipGetLastError());
         return PARO_OK;
     }
-    const int grid = grid_for(pl, on, PARO_TPBK_ADAM);
-    TileSegs segs = segs_for(pl, ob, false);
-    if (dst && mask)
-        hipLaunchKernelGGL((k_adam<true, true>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
-    else if (dst)
-        hipLaunchKernelGGL((k_adam<true, false>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
-    else if (mask)
-        hipLaunchKernelGGL((k_adam<false, true>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
-    else
-        hipLaunchKernelGGL((k_adam<false, false>), dim3(grid), dim3(TPB), 0, st, a, total_sumsq, grad, p, m, v, dst, on, segs);
-    PARO_HIP(hipGetLastError());
+    if (!pl->dev.tile_tab) {              // no per-tile table: the searching kernel over the whole range
+        hipLaunchKernelGGL((k_adam<PACK, true>), dim3(grid_for(on, PARO_TPBK_ADAM)), dim3(TPB), 0, st, a, total_sumsq, grad,
+                           p, m, v, dst, on, segs_for(pl, ob, false), nullptr, 0);
+        PARO_HIP(hipGetLastError());
+        return PARO_OK;
+    }
+    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {      // the table is laid out chunk by chunk
+        const int64_t lo = c * pl->L - ob;
+        const ChunkTiles ct = chunk_tiles(pl, c);
+        uint16_t *d = dst ? dst + lo : nullptr;
+        hipLaunchKernelGGL((k_adam4m<PACK>), dim3(fold4_grid(pl->L)), dim3(64), lds, st, a, total_sumsq, grad + lo, p + lo,
+                           m + lo, v + lo, d, pl->L, ct.tab, pl->dev.no_decay);
+        PARO_HIP(hipGetLastError());
+        if (ct.n_slow == 0) continue;
+        hipLaunchKernelGGL((k_adam<PACK, true>), dim3(grid_for_tiles(ct.n_slow, PARO_TPBK_ADAM)), dim3(TPB), 0, st, a,
+                           total_sumsq, grad + lo, p + lo, m + lo, v + lo, d, pl->L, segs_for(pl, c * pl->L, true), ct.slow,
+                           ct.n_slow);
+        PARO_HIP(hipGetLastError());
+    }
     return PARO_OK;
+}
+
+int do_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, const double *total_sumsq, float *p,
+            float *m, float *v, uint16_t *dst /* nullable: no pack */, hipStream_t st) {
+    return dst ? launch_adam<true>(pl, rank, a, grad, total_sumsq, p, m, v, dst, st)
+               : launch_adam<false>(pl, rank, a, grad, total_sumsq, p, m, v, dst, st);
 }
 
 }  // namespace
@@ -797,6 +994,7 @@ int paro_reduce_shard(paro_plan_t *pl, int rank, const void *const *contrib, int
     if (sumsq_out && (reinterpret_cast<uintptr_t>(sumsq_out) & 7))
         return fail(PARO_EALIGN, "paro_reduce_shard: sumsq_out is not 8-byte aligned");
     if ((rc = ensure_device(pl))) return rc;
+    if (layout == PARO_TENSORS && (rc = ensure_tile_table(pl))) return rc;
     return do_reduce(pl, rank, contrib, layout, grad_out, sumsq_out, static_cast<hipStream_t>(stream));
 }
 
@@ -816,6 +1014,7 @@ int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const floa
     if (dst_base && (reinterpret_cast<uintptr_t>(dst_base) & 15))
         return fail(PARO_EALIGN, "paro_adam_shard: dst_base is not 16-byte aligned");
     if ((rc = ensure_device(pl))) return rc;
+    if (pl->any_no_decay && (rc = ensure_tile_table(pl))) return rc;
     uint16_t *dst = nullptr;
     if (dst_base) {
         int64_t dl, so, sl;
@@ -860,6 +1059,7 @@ int paro_step_fused(paro_plan_t *pl, int rank, const void *const *contrib, int l
             return fail(sumsq_scratch ? PARO_EALIGN : PARO_EINVAL, "paro_step_fused: clipping and skip_nonfinite need sumsq_scratch");
     }
     if ((rc = ensure_device(pl))) return rc;
+    if ((layout == PARO_TENSORS || pl->any_no_decay) && (rc = ensure_tile_table(pl))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t dl, so, sl, ob, on;
     paro_pack_slot(pl, rank, &dl, &so, &sl);
@@ -875,9 +1075,9 @@ int paro_step_fused(paro_plan_t *pl, int rank, const void *const *contrib, int l
         const int64_t lo = c * pl->L - ob;
         src_table(pl, (int)c, contrib, layout, lo, &tab, &gl);
         if (pl->any_no_decay)
-            launch_fused<true>(pl, layout, tab, gl, c * pl->L, a, p + lo, m + lo, v + lo, dst + lo, st);
+            launch_fused<true>(pl, layout, tab, gl, c, a, p + lo, m + lo, v + lo, dst + lo, st);
         else
-            launch_fused<false>(pl, layout, tab, gl, c * pl->L, a, p + lo, m + lo, v + lo, dst + lo, st);
+            launch_fused<false>(pl, layout, tab, gl, c, a, p + lo, m + lo, v + lo, dst + lo, st);
         PARO_HIP(hipGetLastError());
     }
     return PARO_OK;

@@ -8,10 +8,11 @@
 
 #include "paro.h"
 
-// What a tile of a chunk-aligned launch looks like, precomputed so that the kernel does not have
-// to search: tensor >= 0: the whole tile lies inside that tensor, its first element at offset
-// toff; tensor == -1: the tile spans a tensor boundary or padding, first_seg = index of its first
-// non-empty tensor (or the table's end when the tile is all padding).
+// What a tile (2048 consecutive elements) of a chunk looks like, precomputed so that the kernels do
+// not have to search: tensor >= 0: the whole tile lies inside that tensor, its first element at
+// offset toff, first_seg = the tensor's gradient dtype; tensor == -1: the tile holds a tensor
+// boundary (or ends in padding), first_seg = index of its first non-empty tensor; tensor == -2:
+// the tile is all padding.
 struct paro_tile_info {
     int64_t toff;
     int32_t tensor;
@@ -26,8 +27,12 @@ struct paro_device_tables {
     int32_t *nz_tensor = nullptr;   // [n_nz]     index of that tensor in the caller's list
     uint8_t *dtype = nullptr;       // [T]
     uint8_t *no_decay = nullptr;    // [T]
+    // built at the first call that needs them (tensor layout, weight-decay mask):
+    bool tile_tab_tried = false;
     paro_tile_info *tile_tab = nullptr;  // [P * tiles_per_chunk], or null when that would be too large
     int64_t tiles_per_chunk = 0;
+    int32_t *slow_tiles = nullptr;       // per chunk, the tiles with tensor == -1 (index inside the chunk)
+    std::vector<int64_t> slow_start;     // [P + 1] where chunk c's list starts in slow_tiles (host copy)
     double *partials = nullptr;     // per-block partial sums of squares, then the second-level sums
     int64_t n_partials = 0;         // capacity of the first level
 };
