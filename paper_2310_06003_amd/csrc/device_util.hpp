@@ -1,5 +1,5 @@
 // Device-side building blocks of libparo (gfx950): launch-shape and cache-policy knobs, vector
-// types, dtype conversions, streaming loads and stores, the block-wide fp64 sum.  Included by
+// types, dtype conversions, streaming loads and stores, the wave-wide fp64 sum.  Included by
 // kernels.hip only; everything lives in that translation unit's anonymous namespace.
 #pragma once
 
@@ -12,40 +12,32 @@
 
 namespace {
 
-
-// Launch-shape and cache-policy knobs (the defaults are the measured best on MI355X).
+// Cache-policy and occupancy knobs (the defaults are the measured best on MI355X).
 #ifndef PARO_NT_FOLD
 #define PARO_NT_FOLD 1              // streaming (non-temporal) loads for the contributions
 #endif
-#ifndef PARO_NT_STATE
-#define PARO_NT_STATE 0             // ... for g, p, m, v
-#endif
 #ifndef PARO_NT_GSTORE
-#define PARO_NT_GSTORE 1            // ... stores of the reduced gradient in sweep 1
+#define PARO_NT_GSTORE 1            // streaming stores of the reduced gradient in sweep 1
 #endif
-#ifndef PARO_TPBK_FOLD
-#define PARO_TPBK_FOLD 2            // 0: persistent grid-stride blocks; k > 0: block b takes tiles [b*k, b*k + k)
+#ifndef PARO_NT_STATE
+#define PARO_NT_STATE 3             // g, p, m, v in the Adam sweeps: bit 0 streaming loads, bit 1 streaming stores
 #endif
-#ifndef PARO_TPBK_ADAM
-#define PARO_TPBK_ADAM 1
+#ifndef PARO_BATCH
+#define PARO_BATCH 16               // contributions loaded before the first is consumed
 #endif
-#ifndef PARO_G_TRANSPOSE
-#define PARO_G_TRANSPOSE 1          // sweep 1 stores the gradient with whole-wave contiguous 1 KB store instructions
+// One-wave blocks in flight per compute unit (0 = as many as fit).  The mixed read/write sweeps
+// run faster with fewer requests outstanding than the registers would allow.
+#ifndef PARO_FOLD_WAVES_PER_CU
+#define PARO_FOLD_WAVES_PER_CU 14
 #endif
-#ifndef PARO_BLOCKS_PER_CU
-#define PARO_BLOCKS_PER_CU 8
+#ifndef PARO_TFOLD_WAVES_PER_CU
+#define PARO_TFOLD_WAVES_PER_CU 16  // tensor layout: two more dependent look-ups per wave to hide
 #endif
-#ifndef PARO_FOLD4
-#define PARO_FOLD4 1        // sweep 1, chunk layout: the 4-elements-per-thread kernel
+#ifndef PARO_FUSED_WAVES_PER_CU
+#define PARO_FUSED_WAVES_PER_CU 10
 #endif
-#ifndef PARO_FOLD4_TPB
-#define PARO_FOLD4_TPB 64   // its block size (one wave)
-#endif
-#ifndef PARO_FOLD4_WAVES_PER_CU
-#define PARO_FOLD4_WAVES_PER_CU 14   // blocks (waves) of it in flight per compute unit; 0 = no limit
-#endif
-#ifndef PARO_FUSED4_WAVES_PER_CU
-#define PARO_FUSED4_WAVES_PER_CU 10
+#ifndef PARO_ADAM_WAVES_PER_CU
+#define PARO_ADAM_WAVES_PER_CU 12
 #endif
 #ifndef PARO_HOP_WAVES_PER_CU
 #define PARO_HOP_WAVES_PER_CU 0
@@ -53,30 +45,14 @@ namespace {
 #ifndef PARO_COPY_WAVES_PER_CU
 #define PARO_COPY_WAVES_PER_CU 0
 #endif
-#ifndef PARO_ADAM4_WAVES_PER_CU
-#define PARO_ADAM4_WAVES_PER_CU 12
-#endif
-#ifndef PARO_ADAM4
-#define PARO_ADAM4 1        // sweep 2 without a decay mask: the 4-elements-per-thread kernel
-#endif
-#ifndef PARO_NT_ADAM4
-#define PARO_NT_ADAM4 3     // its cache policy: bit 0 streaming loads, bit 1 streaming stores
-#endif
-#ifndef PARO_ADAM4_TPB
-#define PARO_ADAM4_TPB 64   // its block size (one wave)
-#endif
-#ifndef PARO_BATCH_BF16
-#define PARO_BATCH_BF16 16
-#endif
-#ifndef PARO_TPB
-#define PARO_TPB 256
-#endif
 
-constexpr int TPB = PARO_TPB;        // threads per block
-constexpr int EPT = 8;              // elements per thread per tile
-constexpr int TILE = TPB * EPT;     // 2048 with 256 threads
-constexpr int BLOCKS_PER_CU = PARO_BLOCKS_PER_CU;
-constexpr int FINALIZE_CHUNK = 2048;  // partials per block in the first level of the final sum
+constexpr int WAVE = 64;              // threads of a block: every sweep kernel runs in one-wave blocks
+constexpr int EPT = 4;                // elements per thread
+constexpr int PIECE = WAVE * EPT;     // elements per block
+constexpr int TILE = PARO_TILE;       // granularity of the plan's per-tile table
+constexpr int FINALIZE_TPB = 256;     // threads of the kernel that adds the partial sums
+constexpr int FINALIZE_CHUNK = 2048;  // partials per block in its first level
+static_assert(TILE % PIECE == 0, "a block must lie inside one tile");
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -93,14 +69,16 @@ struct AdamConsts {
     int adamw, skip_nonfinite, pack_dtype;
 };
 
-// What the kernels need to map an element of the flat buffer to its tensor.
+// What a launch needs to map its elements to tensors.
 struct TensorMap {
-    const int64_t *nz_off;      // [n_nz + 1]
+    const int64_t *nz_off;      // [n_nz + 1] flat start of every non-empty tensor, then Psi
     const int32_t *nz_tensor;   // [n_nz]
     const uint8_t *dtype;       // [T]
     const uint8_t *no_decay;    // [T]
     int n_nz;
     int64_t total;              // Psi
+    int64_t begin;              // flat index of the launch's element 0
+    const paro_tile_info *tile_tab;   // the per-tile table from the launch's element 0 on, or null
 };
 
 // ---------------------------------------------------------------- small helpers
@@ -123,11 +101,6 @@ template <int DT>
 __device__ __forceinline__ float cvt_hi(unsigned int w) {
     return DT == PARO_F16 ? f16_bits_to_f32(w >> 16) : bf16_hi(w);
 }
-template <int DT>
-__device__ __forceinline__ void unpack16x8(const u32x4 &q, float x[8]) {
-    x[0] = cvt_lo<DT>(q.x); x[1] = cvt_hi<DT>(q.x); x[2] = cvt_lo<DT>(q.y); x[3] = cvt_hi<DT>(q.y);
-    x[4] = cvt_lo<DT>(q.z); x[5] = cvt_hi<DT>(q.z); x[6] = cvt_lo<DT>(q.w); x[7] = cvt_hi<DT>(q.w);
-}
 __device__ __forceinline__ float cvt16(unsigned int h16, int dt) {
     return dt == PARO_F16 ? f16_bits_to_f32(h16) : __uint_as_float(h16 << 16);
 }
@@ -136,6 +109,12 @@ __device__ __forceinline__ unsigned int f32_to_bf16_rne(float f) {
     unsigned int u = __float_as_uint(f);
     if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;      // NaN stays NaN
     return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// two parameters rounded to the low-precision format, packed into one word
+__device__ __forceinline__ unsigned int pack2_lowp(float a, float b, int pack_dtype) {
+    if (pack_dtype == PARO_F16) return f32_to_f16_bits(a) | (f32_to_f16_bits(b) << 16);
+    return f32_to_bf16_rne(a) | (f32_to_bf16_rne(b) << 16);
 }
 
 // Pointers that were themselves loaded from memory carry no address space; these are device
@@ -156,8 +135,6 @@ __device__ __forceinline__ V ld_as(const V *p) {
 }
 template <class Ptr>
 __device__ __forceinline__ auto ld_contrib(Ptr p) { return ld_as<PARO_NT_FOLD != 0>(p); }
-template <class V>
-__device__ __forceinline__ V ld_state(const V *p) { return ld_as<PARO_NT_STATE != 0>(p); }
 template <bool NT, class V>
 __device__ __forceinline__ void st_as(V *p, V v) {
     if (NT)
@@ -166,90 +143,34 @@ __device__ __forceinline__ void st_as(V *p, V v) {
         *p = v;
 }
 
-template <bool NT = (PARO_NT_STATE != 0)>
-__device__ __forceinline__ void load8_f32(const float *p, float x[8]) {
-    f32x4 a = ld_as<NT>(reinterpret_cast<const f32x4 *>(p));
-    f32x4 b = ld_as<NT>(reinterpret_cast<const f32x4 *>(p + 4));
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+// A value that is the same in every lane, marked as such for the compiler (scalar registers,
+// scalar branches, scalar loads of what it indexes).
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uniform(int64_t v) {
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-template <bool NT = false>
-__device__ __forceinline__ void store8_f32(float *p, const float x[8]) {
-    f32x4 a = {x[0], x[1], x[2], x[3]}, b = {x[4], x[5], x[6], x[7]};
-    st_as<NT>(reinterpret_cast<f32x4 *>(p), a);
-    st_as<NT>(reinterpret_cast<f32x4 *>(p + 4), b);
-}
-
-// the low-precision copy of 8 parameters: bf16 or fp16 (block-uniform choice)
-__device__ __forceinline__ void store8_lowp(uint16_t *p, const float x[8], int pack_dtype) {
-    u32x4 w;
-    if (pack_dtype == PARO_F16) {
-        w.x = f32_to_f16_bits(x[0]) | (f32_to_f16_bits(x[1]) << 16);
-        w.y = f32_to_f16_bits(x[2]) | (f32_to_f16_bits(x[3]) << 16);
-        w.z = f32_to_f16_bits(x[4]) | (f32_to_f16_bits(x[5]) << 16);
-        w.w = f32_to_f16_bits(x[6]) | (f32_to_f16_bits(x[7]) << 16);
-    } else {
-        w.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
-        w.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
-        w.z = f32_to_bf16_rne(x[4]) | (f32_to_bf16_rne(x[5]) << 16);
-        w.w = f32_to_bf16_rne(x[6]) | (f32_to_bf16_rne(x[7]) << 16);
-    }
-    *reinterpret_cast<u32x4 *>(p) = w;
-}
-
-// Stores the wave's 512 results so that each of the two store instructions writes 1 KB of
-// consecutive addresses (lane l writes elements 4l..4l+3, then 256+4l..256+4l+3 of the wave's
-// span) instead of every other 16 bytes.  x[0..7] are the lane's elements 8l..8l+7; the values
-// travel between lanes by shuffles.  wave_base = address of the wave's first element.
-template <bool NT>
-__device__ __forceinline__ void store8_f32_wave_contiguous(float *wave_base, const float x[8]) {
-    const int lane = threadIdx.x & 63;
-    const int src_a = lane >> 1, src_b = 32 + (lane >> 1);
-    const bool odd = lane & 1;
-    float a[4], b[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const float lo_a = __shfl(x[i], src_a, 64), hi_a = __shfl(x[4 + i], src_a, 64);
-        const float lo_b = __shfl(x[i], src_b, 64), hi_b = __shfl(x[4 + i], src_b, 64);
-        a[i] = odd ? hi_a : lo_a;
-        b[i] = odd ? hi_b : lo_b;
-    }
-    f32x4 va = {a[0], a[1], a[2], a[3]}, vb = {b[0], b[1], b[2], b[3]};
-    st_as<NT>(reinterpret_cast<f32x4 *>(wave_base + 4 * lane), va);
-    st_as<NT>(reinterpret_cast<f32x4 *>(wave_base + 256 + 4 * lane), vb);
-}
-
-// Sum over the block, valid in thread 0.  Fixed shape: lanes by shuffles, then
-// the waves in order.
-template <int NTHREADS = TPB>
-__device__ __forceinline__ double block_sum(double v) {
+// Sum over the wave, valid in lane 0.  Fixed shape (shuffles by 32, 16, ... 1).
+__device__ __forceinline__ double wave_sum(double v) {
     for (int d = 32; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
-    if constexpr (NTHREADS == 64) {
-        return v;
-    } else {
-        __shared__ double s_wave[NTHREADS / 64];
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        if (lane == 0) s_wave[wave] = v;
-        __syncthreads();
-        double r = 0.0;
-        if (threadIdx.x == 0) {
-            r = s_wave[0];
-            for (int w = 1; w < NTHREADS / 64; ++w) r += s_wave[w];
-        }
-        __syncthreads();
-        return r;
+    return v;
+}
+
+// Sum over a block of FINALIZE_TPB threads, valid in thread 0: lanes by shuffles, then the waves in order.
+__device__ __forceinline__ double block_sum(double v) {
+    __shared__ double s_wave[FINALIZE_TPB / 64];
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) s_wave[wave] = v;
+    __syncthreads();
+    double r = 0.0;
+    if (threadIdx.x == 0) {
+        r = s_wave[0];
+        for (int w = 1; w < FINALIZE_TPB / 64; ++w) r += s_wave[w];
     }
-}
-
-template <class Ld>
-__device__ __forceinline__ int64_t ld_lean_off(const Ld &ld) {
-    if constexpr (Ld::kTensor) return ld.lean_byte_off; else return 0;
-}
-
-template <class Ld>
-__device__ __forceinline__ int ld_lean_dt(const Ld &ld) {
-    if constexpr (Ld::kTensor) return ld.lean_dt; else return PARO_BF16;
+    return r;
 }
 
 // Compile-time loop: the body sees its index as a constant, so arrays indexed by it stay in
@@ -261,13 +182,5 @@ __device__ __forceinline__ void static_for(F &&f) {
         static_for<I + 1, N>(f);
     }
 }
-
-// Where the thread's 8 elements live: tensor (-1 = padding) and offset inside it.
-struct Where8 {
-    int tens[8];
-    int64_t toff[8];
-    bool one_tensor;       // all 8 in one tensor (then tens[0], toff[0] describe them)
-    int first_dt;          // dtype of tens[0] (meaningful when tens[0] >= 0)
-};
 
 }  // namespace

@@ -3,27 +3,31 @@
 //
 // Everything here is bound by HBM bandwidth: per shard parameter the method
 // moves 2P bytes of bf16 contributions and 26-34 bytes of fp32 state, against
-// P adds and ~20 flops.  So the kernels are plain sweeps built around 16-byte
-// coalesced accesses with many independent loads in flight per thread; there
-// is no dense contraction and hence no MFMA.
+// P adds and ~20 flops.  So the kernels are plain sweeps with many independent
+// loads in flight per thread; there is no dense contraction and hence no MFMA.
 //
-//   tile      2048 consecutive elements (256 threads x 8 elements)
-//   grid      one block per run of consecutive tiles (2 for the fold, 1 for
-//             Adam), dispatched in address order: on MI355X this beat
-//             persistent grid-stride blocks by 8-15 % for these mixed
-//             read/write streams (measured; both shapes are kept behind
-//             PARO_TPBK_*)
-//   caches    contributions are read once: streaming (non-temporal) loads;
-//             the reduced gradient is written with streaming stores, each
-//             store instruction of a wave covering 1 KB of consecutive
-//             addresses (values change lanes by shuffles first); p, m, v use
-//             the default policy (streaming hints made sweep 2 slower)
+//   shape     every sweep runs in one-wave blocks (64 threads) of 256 consecutive
+//             elements, 4 per thread: each load or store instruction of a wave
+//             covers 512 B - 1 KB of consecutive addresses (whole cache lines), and
+//             the many short-lived waves, dealt round-robin to the 8 XCDs in
+//             address order, interleave reads and writes finely.  On MI355X this
+//             beat 256-thread blocks of 8-element threads by 8-11 %, and those had
+//             beaten persistent grid-stride blocks by 8-15 %.
+//   occupancy the heavy sweeps ask for unused dynamic LDS so that only 10-14 waves
+//             run per compute unit: fewer requests outstanding fight less over
+//             DRAM pages (another 3-6 %).
+//   caches    everything is touched once: streaming (non-temporal) loads and
+//             stores throughout.
 //   fold      the P contributions of an element are added in a fixed order
 //             (never re-associated, never contracted into FMAs) so the result
 //             is bit-identical to a reduce-scatter ring run in that order
 //   norm      squares are exact in fp64; per-thread fp64 sums -> wave shuffles
-//             -> LDS -> one partial per block -> a one-block kernel adds the
-//             partials in a fixed order.  No atomics: run-to-run identical.
+//             -> one partial per block -> a small kernel adds the partials in a
+//             fixed order, in two levels.  No atomics: run-to-run identical.
+//   tensors   the tensor layout and the weight-decay mask need the tensor an
+//             element belongs to: a per-tile table (built once per plan) answers
+//             for blocks inside one tensor with a single look-up; blocks with a
+//             tensor boundary inside search the offset table lane by lane.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -76,91 +80,99 @@ __device__ __forceinline__ void adam1(const AdamConsts &a, float sc, bool decays
     }
 }
 
-// Which tiles a block takes: a run of TPBK consecutive tiles of the launch's range, or, when the
-// launch comes with a list of tiles, a run of TPBK entries of that list.
-#define TILE_LOOP(TPBK, tile, ntiles, list, n_list)                                                          \
-    for (int64_t it_ = (int64_t)blockIdx.x * (TPBK),                                                         \
-                 it_end_ = min((list) ? (int64_t)(n_list) : (int64_t)(ntiles), it_ + (TPBK)), tile = 0;      \
-         it_ < it_end_ && ((tile = (list) ? (int64_t)(list)[it_] : it_), true); ++it_)
+constexpr bool STATE_LNT = (PARO_NT_STATE & 1) != 0, STATE_SNT = (PARO_NT_STATE & 2) != 0;
 
-// --------------------------------------------------------------------- kernels
-// Sweep 1: g = fold of the contributions; optional per-block partial of sum g^2.
-template <class Ld, bool SUMSQ>
-__global__ __launch_bounds__(TPB) void k_reduce(Ld ld, const SrcTable src, int P, int group_len, int64_t n,
-                                                float *__restrict__ g, double *__restrict__ partials,
-                                                TileSegs segs, const int32_t *__restrict__ tile_list, int n_list) {
-    __shared__ int64_t s_off[Ld::kTensor ? TILE + 2 : 1];
-    __shared__ int s_head[2];
-    __shared__ uintptr_t s_ptr[Ld::kTensor ? PARO_MAX_RANKS : 1];
-    segs.s_off = s_off;
-    segs.s_head = s_head;
-    double acc = 0.0;
-    const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles, tile_list, n_list) {
-        if (Ld::kTensor) {
-            segs.begin_tile(tile * TILE);
-            ld.begin_tile(segs, src, P, s_ptr);
-        }
-        const int rel0 = threadIdx.x * EPT;
-        const int64_t e = tile * TILE + rel0;
-        if (e < n) {
-            Where8 w;
-            if (Ld::kTensor) locate8(segs, rel0, w);
-            ld.prepare(e, w);
-            float X[8];
-            if (Ld::kTensor && ld.lean()) {
-                if (ld_lean_dt(ld) == PARO_F16) {
-                    Staged16Loader<PARO_F16> lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
-                    fold8<Staged16Loader<PARO_F16>, false>(lean, src, P, group_len, X);
-                } else {
-                    Staged16Loader<PARO_BF16> lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
-                    fold8<Staged16Loader<PARO_BF16>, false>(lean, src, P, group_len, X);
-                }
-            } else if (Ld::kTensor && !__all(w.one_tensor)) {
-                fold8<Ld, true>(ld, src, P, group_len, X);
-            } else {
-                fold8<Ld, false>(ld, src, P, group_len, X);
-            }
-            // n is a multiple of 8 but a wave's 512-element span may be cut by the end of the range;
-            // only whole spans take the transposed path (the test is wave-uniform)
-            const int64_t wave_first = tile * TILE + (threadIdx.x & ~63) * EPT;
-            if (PARO_G_TRANSPOSE && wave_first + 64 * EPT <= n)
-                store8_f32_wave_contiguous<PARO_NT_GSTORE != 0>(g + wave_first, X);
-            else
-                store8_f32<PARO_NT_GSTORE != 0>(g + e, X);
-            if (SUMSQ) {
+struct State4 { f32x4 p, m, v; };
+
+__device__ __forceinline__ State4 load_state4(const float *p, const float *m, const float *v, int64_t e) {
+    State4 s;
+    s.p = ld_as<STATE_LNT>(reinterpret_cast<const f32x4 *>(p + e));
+    s.m = ld_as<STATE_LNT>(reinterpret_cast<const f32x4 *>(m + e));
+    s.v = ld_as<STATE_LNT>(reinterpret_cast<const f32x4 *>(v + e));
+    return s;
+}
+
+// Adam on the thread's 4 elements; state and (optionally) the low-precision copy written back.
+template <bool PACK>
+__device__ __forceinline__ void update4(const AdamConsts &a, float sc, const bool decays[4], const float gg[4],
+                                        const State4 &s, float *p, float *m, float *v, uint16_t *dst, int64_t e) {
+    float pp[4] = {s.p.x, s.p.y, s.p.z, s.p.w}, mm[4] = {s.m.x, s.m.y, s.m.z, s.m.w},
+          vv[4] = {s.v.x, s.v.y, s.v.z, s.v.w};
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc += (double)X[i] * (double)X[i];
-            }
-        }
-    }
-    if (SUMSQ) {
-        const double s = block_sum(acc);
-        if (threadIdx.x == 0) partials[blockIdx.x] = s;
+    for (int i = 0; i < 4; ++i) adam1(a, sc, decays[i], gg[i], pp[i], mm[i], vv[i]);
+    st_as<STATE_SNT>(reinterpret_cast<f32x4 *>(p + e), f32x4{pp[0], pp[1], pp[2], pp[3]});
+    st_as<STATE_SNT>(reinterpret_cast<f32x4 *>(m + e), f32x4{mm[0], mm[1], mm[2], mm[3]});
+    st_as<STATE_SNT>(reinterpret_cast<f32x4 *>(v + e), f32x4{vv[0], vv[1], vv[2], vv[3]});
+    if (PACK) {
+        const u32x2 w = {pack2_lowp(pp[0], pp[1], a.pack_dtype), pack2_lowp(pp[2], pp[3], a.pack_dtype)};
+        st_as<STATE_SNT>(reinterpret_cast<u32x2 *>(dst + e), w);
     }
 }
 
-// Sweep 1 for the chunk layout: 4 elements per thread in one-wave blocks.  Every load
-// instruction of a wave covers 512 (2-byte dtypes) or 1024 consecutive bytes, the store 1 KB,
-// and the many short-lived waves interleave reads and writes more finely than 8-element
-// threads in 256-thread blocks did (measured: 3-4 % faster at P = 16).
+// Which of the thread's 4 elements take weight decay (padding does, and stays 0).
+__device__ __forceinline__ void decay_flags(const TensorMap &tm, const Piece &pc, int64_t e, bool decays[4]) {
+    if (pc.tensor != -1) {
+        const bool d = pc.tensor < 0 || tm.no_decay[pc.tensor] == 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) decays[i] = d;
+    } else {
+        int tens[4];
+        int64_t toff[4];
+        locate4(tm, pc.seg, tm.begin + e, tens, toff);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) decays[i] = tens[i] < 0 || tm.no_decay[tens[i]] == 0;
+    }
+}
+
+// The thread's first element; n (the launch's length) is a multiple of 8, so a thread's 4
+// elements are all inside the range or all outside.
+__device__ __forceinline__ int64_t block_first() { return (int64_t)blockIdx.x * PIECE; }
+
+__device__ __forceinline__ double sumsq4(const float X[4]) {
+    double acc = 0.0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc += (double)X[i] * (double)X[i];
+    return acc;
+}
+
+// --------------------------------------------------------------------- kernels
+// Sweep 1, chunk layout: g = fold of the contributions; optional per-block partial of sum g^2.
 template <int DT, bool SUMSQ>
-__global__ __launch_bounds__(PARO_FOLD4_TPB) void k_reduce4(const SrcTable src, int P, int group_len, int64_t n,
-                                                            float *__restrict__ g, double *__restrict__ partials) {
-    const int64_t e = ((int64_t)blockIdx.x * PARO_FOLD4_TPB + threadIdx.x) * 4;     // n is a multiple of 8
+__global__ __launch_bounds__(WAVE) void k_reduce4(const SrcTable src, int P, int group_len, int64_t n,
+                                                  float *__restrict__ g, double *__restrict__ partials) {
+    const int64_t e = block_first() + threadIdx.x * EPT;
     double acc = 0.0;
     if (e < n) {
         Chunk4Loader<DT> ld{e};
         float X[4];
-        fold8<Chunk4Loader<DT>, false>(ld, src, P, group_len, X);
+        fold4(ld, src, P, group_len, X);
         st_as<PARO_NT_GSTORE != 0>(reinterpret_cast<f32x4 *>(g + e), f32x4{X[0], X[1], X[2], X[3]});
-        if (SUMSQ) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc += (double)X[i] * (double)X[i];
+        if (SUMSQ) acc = sumsq4(X);
+    }
+    if (SUMSQ) {
+        const double s = wave_sum(acc);
+        if (threadIdx.x == 0) partials[blockIdx.x] = s;
+    }
+}
+
+// Sweep 1, tensor layout.
+template <bool SUMSQ>
+__global__ __launch_bounds__(WAVE) void k_reduce4t(const SrcTable src, int P, int group_len, int64_t n,
+                                                   float *__restrict__ g, double *__restrict__ partials,
+                                                   const TensorMap tm) {
+    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    double acc = 0.0;
+    if (e0 < n) {                                            // wave-uniform
+        const Piece pc = piece_of(tm, e0, n);
+        if (e < n) {
+            float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};           // padding: the sum of zeros
+            if (pc.tensor != -2) fold_tensors(tm, pc, e, src, P, group_len, X);
+            st_as<PARO_NT_GSTORE != 0>(reinterpret_cast<f32x4 *>(g + e), f32x4{X[0], X[1], X[2], X[3]});
+            if (SUMSQ) acc = sumsq4(X);
         }
     }
     if (SUMSQ) {
-        const double s = block_sum<PARO_FOLD4_TPB>(acc);
+        const double s = wave_sum(acc);
         if (threadIdx.x == 0) partials[blockIdx.x] = s;
     }
 }
@@ -168,13 +180,14 @@ __global__ __launch_bounds__(PARO_FOLD4_TPB) void k_reduce4(const SrcTable src, 
 // Adds partials in a fixed order: block b takes the slice [b*chunk, b*chunk + chunk) of the n
 // values; thread t adds its slice's elements t, t+T, t+2T, ... (eight loads in flight at a time,
 // added in index order); then the fixed block tree.  Launched as many-blocks -> one block.
-__global__ __launch_bounds__(TPB) void k_finalize(const double *__restrict__ partials, int n, int chunk, double *out) {
+__global__ __launch_bounds__(FINALIZE_TPB) void k_finalize(const double *__restrict__ partials, int n, int chunk,
+                                                           double *out) {
     const int lo = blockIdx.x * chunk, hi = min(n, lo + chunk);
     double acc = 0.0;
-    for (int k0 = lo + threadIdx.x; k0 < hi; k0 += 8 * TPB) {
+    for (int k0 = lo + threadIdx.x; k0 < hi; k0 += 8 * FINALIZE_TPB) {
         double x[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = (k0 + u * TPB < hi) ? partials[k0 + u * TPB] : 0.0;
+        for (int u = 0; u < 8; ++u) x[u] = (k0 + u * FINALIZE_TPB < hi) ? partials[k0 + u * FINALIZE_TPB] : 0.0;
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += x[u];
     }
@@ -182,356 +195,74 @@ __global__ __launch_bounds__(TPB) void k_finalize(const double *__restrict__ par
     if (threadIdx.x == 0) out[blockIdx.x] = s;
 }
 
-// Sweep 2: Adam on the stored gradient, optionally packing bf16 parameters and
-// optionally with a per-tensor weight-decay mask.
+// Sweep 2: Adam on the stored gradient, optionally packing the low-precision parameters.
+// MASK: some tensors are exempt from weight decay.
 template <bool PACK, bool MASK>
-__global__ __launch_bounds__(TPB) void k_adam(const AdamConsts a, const double *__restrict__ total_sumsq,
-                                              const float *__restrict__ g, float *__restrict__ p,
-                                              float *__restrict__ m, float *__restrict__ v,
-                                              uint16_t *__restrict__ dst, int64_t n, TileSegs segs,
-                                              const int32_t *__restrict__ tile_list, int n_list) {
-    __shared__ int64_t s_off[MASK ? TILE + 2 : 1];
-    __shared__ int s_head[2];
-    segs.s_off = s_off;
-    segs.s_head = s_head;
+__global__ __launch_bounds__(WAVE) void k_adam4(const AdamConsts a, const double *__restrict__ total_sumsq,
+                                                const float *__restrict__ g, float *__restrict__ p,
+                                                float *__restrict__ m, float *__restrict__ v,
+                                                uint16_t *__restrict__ dst, int64_t n, const TensorMap tm) {
     // an overflowed (non-finite) gradient makes its sum of squares non-finite: the whole step is skipped
     if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
     const float sc = scale_from_norm(a, total_sumsq);
-    const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_ADAM, tile, ntiles, tile_list, n_list) {
-        if (MASK) segs.begin_tile(tile * TILE);
-        const int rel0 = threadIdx.x * EPT;
-        const int64_t e = tile * TILE + rel0;
-        if (e < n) {
-            bool decays[8];
-            if (MASK) {
-                Where8 w;
-                locate8(segs, rel0, w);
-#pragma unroll
-                for (int i = 0; i < 8; ++i) decays[i] = w.tens[i] < 0 || segs.tm.no_decay[w.tens[i]] == 0;
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) decays[i] = true;
-            }
-            float gg[8], pp[8], mm[8], vv[8];
-            load8_f32(g + e, gg);
-            load8_f32(p + e, pp);
-            load8_f32(m + e, mm);
-            load8_f32(v + e, vv);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) adam1(a, sc, decays[i], gg[i], pp[i], mm[i], vv[i]);
-            store8_f32(p + e, pp);
-            store8_f32(m + e, mm);
-            store8_f32(v + e, vv);
-            if (PACK) store8_lowp(dst + e, pp, a.pack_dtype);
-        }
-    }
-}
-
-// ---- 4 elements per thread, one-wave blocks: the shape of the sweeps that need no per-element
-// look-up (chunk layout, no tensor exempt from weight decay).  Every load and store instruction
-// of a wave covers 1 KB of consecutive addresses (512 B for 2-byte data) - whole cache lines,
-// which is what lets the streaming policy be used both ways without partial-line writes.
-constexpr bool ADAM4_LNT = (PARO_NT_ADAM4 & 1) != 0, ADAM4_SNT = (PARO_NT_ADAM4 & 2) != 0;
-
-struct State4 { f32x4 p, m, v; };
-
-__device__ __forceinline__ State4 load_state4(const float *p, const float *m, const float *v, int64_t e) {
-    State4 s;
-    s.p = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(p + e));
-    s.m = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(m + e));
-    s.v = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(v + e));
-    return s;
-}
-
-// Adam on the thread's 4 elements, state and (optionally) the low-precision copy written back.
-template <bool PACK>
-__device__ __forceinline__ void update4(const AdamConsts &a, float sc, bool decays, const float gg[4], const State4 &s,
-                                        float *p, float *m, float *v, uint16_t *dst, int64_t e) {
-    float pp[4] = {s.p.x, s.p.y, s.p.z, s.p.w}, mm[4] = {s.m.x, s.m.y, s.m.z, s.m.w},
-          vv[4] = {s.v.x, s.v.y, s.v.z, s.v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) adam1(a, sc, decays, gg[i], pp[i], mm[i], vv[i]);
-    st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(p + e), f32x4{pp[0], pp[1], pp[2], pp[3]});
-    st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(m + e), f32x4{mm[0], mm[1], mm[2], mm[3]});
-    st_as<ADAM4_SNT>(reinterpret_cast<f32x4 *>(v + e), f32x4{vv[0], vv[1], vv[2], vv[3]});
-    if (PACK) {
-        u32x2 w;
-        if (a.pack_dtype == PARO_F16) {
-            w.x = f32_to_f16_bits(pp[0]) | (f32_to_f16_bits(pp[1]) << 16);
-            w.y = f32_to_f16_bits(pp[2]) | (f32_to_f16_bits(pp[3]) << 16);
-        } else {
-            w.x = f32_to_bf16_rne(pp[0]) | (f32_to_bf16_rne(pp[1]) << 16);
-            w.y = f32_to_bf16_rne(pp[2]) | (f32_to_bf16_rne(pp[3]) << 16);
-        }
-        st_as<ADAM4_SNT>(reinterpret_cast<u32x2 *>(dst + e), w);
-    }
-}
-
-// Sweep 2 without a decay mask.
-template <bool PACK>
-__global__ __launch_bounds__(PARO_ADAM4_TPB) void k_adam4(const AdamConsts a, const double *__restrict__ total_sumsq,
-                                                          const float *__restrict__ g, float *__restrict__ p,
-                                                          float *__restrict__ m, float *__restrict__ v,
-                                                          uint16_t *__restrict__ dst, int64_t n) {
-    if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
-    const float sc = scale_from_norm(a, total_sumsq);
-    const int64_t e = ((int64_t)blockIdx.x * PARO_ADAM4_TPB + threadIdx.x) * 4;      // n is a multiple of 8
-    if (e >= n) return;
-    const f32x4 G = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(g + e));
-    const State4 s = load_state4(p, m, v, e);
-    const float gg[4] = {G.x, G.y, G.z, G.w};
-    update4<PACK>(a, sc, true, gg, s, p, m, v, dst, e);
-}
-
-// Single sweep (no clipping), chunk layout, no decay mask: fold, Adam and pack.
-template <int DT>
-__global__ __launch_bounds__(PARO_FOLD4_TPB) void k_fused4(const SrcTable src, int P, int group_len, int64_t n,
-                                                           const AdamConsts a, float *__restrict__ p,
-                                                           float *__restrict__ m, float *__restrict__ v,
-                                                           uint16_t *__restrict__ dst) {
-    const int64_t e = ((int64_t)blockIdx.x * PARO_FOLD4_TPB + threadIdx.x) * 4;
-    if (e >= n) return;
-    const State4 s = load_state4(p, m, v, e);
-    Chunk4Loader<DT> ld{e};
-    float X[4];
-    fold8<Chunk4Loader<DT>, false>(ld, src, P, group_len, X);
-    update4<true>(a, a.grad_scale, true, X, s, p, m, v, dst, e);
-}
-
-// ---- the one-wave shape for work that depends on the tensor an element belongs to (tensor
-// layout, weight-decay mask).  The plan's per-tile table says, for every 2048-element tile of a
-// chunk, whether it lies inside one tensor (then the 8 one-wave blocks of the tile know their
-// tensor and offset without any search), is all padding, or holds a tensor boundary.  Boundary
-// tiles are left to the tile-at-a-time kernels, which then run over the plan's list of such
-// tiles only; the blocks here return at once for them.
-struct Piece {
-    int tensor;        // >= 0: the block's 256 elements lie in this tensor; -1: boundary tile; -2: padding
-    int dt;            // the tensor's gradient dtype
-    int64_t toff;      // offset of the block's first element inside the tensor
-};
-
-__device__ __forceinline__ Piece piece_of(const paro_tile_info *__restrict__ tile_tab, int64_t e0) {
-    const paro_tile_info info = tile_tab[e0 / TILE];           // one address for the whole wave
+    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    if (e0 >= n) return;
+    bool decays[4] = {true, true, true, true};
     Piece pc;
-    pc.tensor = __builtin_amdgcn_readfirstlane(info.tensor);  // tell the compiler: wave-uniform
-    pc.dt = __builtin_amdgcn_readfirstlane(info.first_seg);
-    const int64_t toff = info.toff + (e0 % TILE);
-    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)toff);
-    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uint64_t)toff >> 32));
-    pc.toff = (int64_t)(((uint64_t)hi << 32) | lo);
-    return pc;
-}
-
-// 4 elements per thread out of one tensor's per-rank gradients.  ALIGNED: every rank's first byte
-// for this block is 8-byte (2-byte dtypes) or 16-byte (fp32) aligned, so one vector load fetches
-// the thread's 4 values; otherwise element loads.
-template <int DT, bool ALIGNED>
-struct Tensor4Loader {
-    static constexpr bool kTensor = false;
-    static constexpr int kElems = 4;
-    static constexpr int kBatch = PARO_BATCH_BF16;
-    using Raw = std::conditional_t<DT == PARO_F32, u32x4, u32x2>;
-    int tensor;
-    int64_t byte_off;          // of the thread's first element inside the tensor
-    template <bool SLOW>
-    __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
-        const uintptr_t base = static_cast<const uintptr_t *>(src.p[k])[tensor] + (uintptr_t)byte_off;
-        if constexpr (ALIGNED) {
-            r = ld_contrib(global_ptr<Raw>(base));
-        } else if constexpr (DT != PARO_F32) {
-            const auto *h = global_ptr<uint16_t>(base);
-            r.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
-            r.y = (unsigned)h[2] | ((unsigned)h[3] << 16);
-        } else {
-            const auto *w = global_ptr<unsigned int>(base);
-            r = u32x4{w[0], w[1], w[2], w[3]};
-        }
-    }
-    template <bool SLOW>
-    __device__ __forceinline__ void unpack(const SrcTable &s, int k, const Raw &r, float x[4]) const {
-        Chunk4Loader<DT>{0}.template unpack<SLOW>(s, k, r, x);
-    }
-};
-
-template <int DT>
-__device__ __forceinline__ void fold_piece_dt(const Piece &pc, const SrcTable &src, int P, int group_len, float X[4]) {
-    constexpr int ESIZE = DT == PARO_F32 ? 4 : 2;
-    constexpr uintptr_t NEED = DT == PARO_F32 ? 15 : 7;
-    bool aligned = true;                                         // wave-uniform
-    for (int k = 0; k < P; ++k) {
-        const uintptr_t b = static_cast<const uintptr_t *>(src.p[k])[pc.tensor];
-        aligned = aligned && ((b + (uintptr_t)pc.toff * ESIZE) & NEED) == 0;
-    }
-    const int64_t byte_off = (pc.toff + (int64_t)threadIdx.x * 4) * ESIZE;
-    if (aligned) {
-        Tensor4Loader<DT, true> ld{pc.tensor, byte_off};
-        fold8<Tensor4Loader<DT, true>, false>(ld, src, P, group_len, X);
-    } else {
-        Tensor4Loader<DT, false> ld{pc.tensor, byte_off};
-        fold8<Tensor4Loader<DT, false>, false>(ld, src, P, group_len, X);
-    }
-}
-
-// The ordered fold for a block whose elements lie in one tensor (pc.tensor >= 0).
-__device__ __forceinline__ void fold_piece(const Piece &pc, const SrcTable &src, int P, int group_len, float X[4]) {
-    if (pc.dt == PARO_BF16) fold_piece_dt<PARO_BF16>(pc, src, P, group_len, X);
-    else if (pc.dt == PARO_F16) fold_piece_dt<PARO_F16>(pc, src, P, group_len, X);
-    else fold_piece_dt<PARO_F32>(pc, src, P, group_len, X);
-}
-
-// Sweep 1, tensor layout, tiles that lie in one tensor or in the padding.  Every block writes its
-// partial sum (0 for a block that leaves its tile to the boundary-tile launch).
-template <bool SUMSQ>
-__global__ __launch_bounds__(64) void k_reduce4t(const SrcTable src, int P, int group_len, int64_t n,
-                                                 float *__restrict__ g, double *__restrict__ partials,
-                                                 const paro_tile_info *__restrict__ tile_tab) {
-    const int64_t e0 = (int64_t)blockIdx.x * 256, e = e0 + (int64_t)threadIdx.x * 4;
-    const Piece pc = piece_of(tile_tab, e0);
-    double acc = 0.0;
-    if (pc.tensor != -1 && e < n) {
-        float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};                   // padding: the sum of zeros
-        if (pc.tensor >= 0) fold_piece(pc, src, P, group_len, X);
-        st_as<PARO_NT_GSTORE != 0>(reinterpret_cast<f32x4 *>(g + e), f32x4{X[0], X[1], X[2], X[3]});
-        if (SUMSQ) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc += (double)X[i] * (double)X[i];
-        }
-    }
-    if (SUMSQ) {
-        const double s = block_sum<64>(acc);
-        if (threadIdx.x == 0) partials[blockIdx.x] = s;
-    }
-}
-
-// Sweep 2 with a weight-decay mask, same tiles.
-template <bool PACK>
-__global__ __launch_bounds__(64) void k_adam4m(const AdamConsts a, const double *__restrict__ total_sumsq,
-                                               const float *__restrict__ g, float *__restrict__ p,
-                                               float *__restrict__ m, float *__restrict__ v,
-                                               uint16_t *__restrict__ dst, int64_t n,
-                                               const paro_tile_info *__restrict__ tile_tab,
-                                               const uint8_t *__restrict__ no_decay) {
-    if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
-    const float sc = scale_from_norm(a, total_sumsq);
-    const int64_t e0 = (int64_t)blockIdx.x * 256, e = e0 + (int64_t)threadIdx.x * 4;
+    if (MASK) pc = piece_of(tm, e0, n);
     if (e >= n) return;
-    const Piece pc = piece_of(tile_tab, e0);
-    if (pc.tensor == -1) return;
-    const bool decays = pc.tensor < 0 || no_decay[pc.tensor] == 0;      // padding decays (and stays 0)
-    const f32x4 G = ld_as<ADAM4_LNT>(reinterpret_cast<const f32x4 *>(g + e));
+    const f32x4 G = ld_as<STATE_LNT>(reinterpret_cast<const f32x4 *>(g + e));
     const State4 s = load_state4(p, m, v, e);
+    if (MASK) decay_flags(tm, pc, e, decays);
     const float gg[4] = {G.x, G.y, G.z, G.w};
     update4<PACK>(a, sc, decays, gg, s, p, m, v, dst, e);
 }
 
-// Single sweep (no clipping) for the tensor layout and / or a weight-decay mask, same tiles.
-// TENSORS: contributions are per-tensor gradients; else arrays in shard coordinates of dtype DT.
+// Single sweep when nothing has to wait for the norm (no clipping): fold, Adam and pack; the
+// reduced gradient never goes to memory.  TENSORS: contributions are per-tensor gradients; else
+// arrays in shard coordinates of dtype DT.
 template <bool TENSORS, int DT, bool MASK>
-__global__ __launch_bounds__(64) void k_fused4t(const SrcTable src, int P, int group_len, int64_t n, const AdamConsts a,
-                                                float *__restrict__ p, float *__restrict__ m, float *__restrict__ v,
-                                                uint16_t *__restrict__ dst,
-                                                const paro_tile_info *__restrict__ tile_tab,
-                                                const uint8_t *__restrict__ no_decay) {
-    const int64_t e0 = (int64_t)blockIdx.x * 256, e = e0 + (int64_t)threadIdx.x * 4;
+__global__ __launch_bounds__(WAVE) void k_fused4(const SrcTable src, int P, int group_len, int64_t n,
+                                                 const AdamConsts a, float *__restrict__ p, float *__restrict__ m,
+                                                 float *__restrict__ v, uint16_t *__restrict__ dst,
+                                                 const TensorMap tm) {
+    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    if (e0 >= n) return;
+    Piece pc;
+    if (TENSORS || MASK) pc = piece_of(tm, e0, n);
     if (e >= n) return;
-    const Piece pc = piece_of(tile_tab, e0);
-    if (pc.tensor == -1) return;
-    const bool decays = !MASK || pc.tensor < 0 || no_decay[pc.tensor] == 0;
     const State4 s = load_state4(p, m, v, e);
     float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if constexpr (TENSORS) {
-        if (pc.tensor >= 0) fold_piece(pc, src, P, group_len, X);
+        if (pc.tensor != -2) fold_tensors(tm, pc, e, src, P, group_len, X);
     } else {
         Chunk4Loader<DT> ld{e};
-        fold8<Chunk4Loader<DT>, false>(ld, src, P, group_len, X);
+        fold4(ld, src, P, group_len, X);
     }
+    bool decays[4] = {true, true, true, true};
+    if (MASK) decay_flags(tm, pc, e, decays);
     update4<true>(a, a.grad_scale, decays, X, s, p, m, v, dst, e);
 }
 
-// Single sweep when nothing has to wait for the norm: fold, Adam and pack; the
-// reduced gradient never goes to memory.
-template <class Ld, bool MASK>
-__global__ __launch_bounds__(TPB) void k_fused(Ld ld, const SrcTable src, int P, int group_len, int64_t n,
-                                               const AdamConsts a, float *__restrict__ p, float *__restrict__ m,
-                                               float *__restrict__ v, uint16_t *__restrict__ dst, TileSegs segs,
-                                               const int32_t *__restrict__ tile_list, int n_list) {
-    constexpr bool NEED_SEGS = Ld::kTensor || MASK;
-    __shared__ int64_t s_off[NEED_SEGS ? TILE + 2 : 1];
-    __shared__ int s_head[2];
-    __shared__ uintptr_t s_ptr[Ld::kTensor ? PARO_MAX_RANKS : 1];
-    segs.s_off = s_off;
-    segs.s_head = s_head;
-    const float sc = a.grad_scale;                     // no clipping on this path
-    const int64_t ntiles = (n + TILE - 1) / TILE;
-    TILE_LOOP(PARO_TPBK_FOLD, tile, ntiles, tile_list, n_list) {
-        if (NEED_SEGS) segs.begin_tile(tile * TILE);
-        if (Ld::kTensor) ld.begin_tile(segs, src, P, s_ptr);
-        const int rel0 = threadIdx.x * EPT;
-        const int64_t e = tile * TILE + rel0;
-        if (e < n) {
-            Where8 w;
-            if (NEED_SEGS) locate8(segs, rel0, w);
-            ld.prepare(e, w);
-            float pp[8], mm[8], vv[8], X[8];
-            load8_f32(p + e, pp);
-            load8_f32(m + e, mm);
-            load8_f32(v + e, vv);
-            if (Ld::kTensor && ld.lean()) {
-                if (ld_lean_dt(ld) == PARO_F16) {
-                    Staged16Loader<PARO_F16> lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
-                    fold8<Staged16Loader<PARO_F16>, false>(lean, src, P, group_len, X);
-                } else {
-                    Staged16Loader<PARO_BF16> lean{s_ptr, ld_lean_off(ld) + (int64_t)rel0 * 2};
-                    fold8<Staged16Loader<PARO_BF16>, false>(lean, src, P, group_len, X);
-                }
-            } else if (Ld::kTensor && !__all(w.one_tensor)) {
-                fold8<Ld, true>(ld, src, P, group_len, X);
-            } else {
-                fold8<Ld, false>(ld, src, P, group_len, X);
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                bool decays = true;
-                if (MASK) decays = w.tens[i] < 0 || segs.tm.no_decay[w.tens[i]] == 0;
-                adam1(a, sc, decays, X[i], pp[i], mm[i], vv[i]);
-            }
-            store8_f32(p + e, pp);
-            store8_f32(m + e, mm);
-            store8_f32(v + e, vv);
-            store8_lowp(dst + e, pp, a.pack_dtype);
-        }
-    }
-}
-
-// Low-precision pack alone: one-wave blocks, 4 elements per thread.
-__global__ __launch_bounds__(64) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n,
-                                             int pack_dtype) {
-    const int64_t e = ((int64_t)blockIdx.x * 64 + threadIdx.x) * 4;          // n is a multiple of 8
+// Low-precision pack alone.
+__global__ __launch_bounds__(WAVE) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n,
+                                               int pack_dtype) {
+    const int64_t e = block_first() + threadIdx.x * EPT;
     if (e >= n) return;
     const f32x4 P = ld_as<true>(reinterpret_cast<const f32x4 *>(p + e));
-    u32x2 w;
-    if (pack_dtype == PARO_F16) {
-        w.x = f32_to_f16_bits(P.x) | (f32_to_f16_bits(P.y) << 16);
-        w.y = f32_to_f16_bits(P.z) | (f32_to_f16_bits(P.w) << 16);
-    } else {
-        w.x = f32_to_bf16_rne(P.x) | (f32_to_bf16_rne(P.y) << 16);
-        w.y = f32_to_bf16_rne(P.z) | (f32_to_bf16_rne(P.w) << 16);
-    }
+    const u32x2 w = {pack2_lowp(P.x, P.y, pack_dtype), pack2_lowp(P.z, P.w, pack_dtype)};
     st_as<true>(reinterpret_cast<u32x2 *>(dst + e), w);
 }
 
-// One ring hop / one accumulation: out = a + b, element by element in fp32.  One-wave blocks,
-// 4 elements per thread, streaming loads and stores.
+// One ring hop / one accumulation: out = a + b, element by element in fp32.
 template <int DT>
 __device__ __forceinline__ void hop_load4(const void *a, int64_t e, float x[4]) {
-    if (DT != PARO_F32) {
-        const u32x2 q = ld_as<true>(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(a) + e));
-        x[0] = cvt_lo<DT>(q.x); x[1] = cvt_hi<DT>(q.x); x[2] = cvt_lo<DT>(q.y); x[3] = cvt_hi<DT>(q.y);
-    } else {
-        const f32x4 q = ld_as<true>(reinterpret_cast<const f32x4 *>(static_cast<const float *>(a) + e));
-        x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
-    }
+    typename Chunk4Loader<DT>::Raw r;
+    if constexpr (DT != PARO_F32)
+        r = ld_as<true>(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(a) + e));
+    else
+        r = ld_as<true>(reinterpret_cast<const u32x4 *>(static_cast<const float *>(a) + e));
+    Chunk4Loader<DT>::to_f32(r, x);
 }
 template <int DT>
 __device__ __forceinline__ float hop_load1(const void *a, int64_t i) {
@@ -539,9 +270,9 @@ __device__ __forceinline__ float hop_load1(const void *a, int64_t i) {
 }
 
 template <int DA, int DB>
-__global__ __launch_bounds__(64) void k_hop(const void *a, const void *b, float *out, int64_t n) {
-    const int64_t e = ((int64_t)blockIdx.x * 64 + threadIdx.x) * 4;
-    if (e + 4 <= n) {
+__global__ __launch_bounds__(WAVE) void k_hop(const void *a, const void *b, float *out, int64_t n) {
+    const int64_t e = block_first() + threadIdx.x * EPT;
+    if (e + EPT <= n) {
         float x[4], y[4];
         hop_load4<DA>(a, e, x);
         hop_load4<DB>(b, e, y);
@@ -552,8 +283,8 @@ __global__ __launch_bounds__(64) void k_hop(const void *a, const void *b, float 
 }
 
 // Plain copy of n 16-byte units (an all-gather message landing in the parameter buffer).
-__global__ __launch_bounds__(64) void k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * 64 + threadIdx.x;
+__global__ __launch_bounds__(WAVE) void k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * WAVE + threadIdx.x;
     if (i < n) st_as<true>(dst + i, ld_as<true>(src + i));
 }
 
@@ -578,15 +309,14 @@ int check_ptr(const void *p, const char *what) {
     return PARO_OK;
 }
 
-// Blocks of the 4-elements-per-thread fold over n elements.
-int fold4_grid(int64_t n) {
-    const int64_t per_block = 4 * (int64_t)PARO_FOLD4_TPB;
-    const int64_t nb = (n + per_block - 1) / per_block;
-    return (int)(nb < 1 ? 1 : nb);
+// One-wave blocks of a sweep over n elements.
+unsigned piece_grid(int64_t n) {
+    const int64_t nb = (n + PIECE - 1) / PIECE;
+    return (unsigned)(nb < 1 ? 1 : nb);
 }
 
 // Occupancy throttle for the one-wave-block sweeps: on this part the mixed read/write sweeps run
-// faster with 12-14 waves per compute unit in flight than with the 32 the registers would allow
+// faster with 10-14 waves per compute unit in flight than with the 32 the registers would allow
 // (fewer requests fighting over DRAM pages).  The launch asks for dynamic LDS it never touches,
 // sized so that only `waves_per_cu` blocks fit on a compute unit.
 unsigned throttle_lds(const paro_plan_t *pl, int waves_per_cu) {
@@ -609,7 +339,6 @@ void free_tables(paro_device_tables &d) {
     (void)hipFree(d.dtype);
     (void)hipFree(d.no_decay);
     (void)hipFree(d.tile_tab);
-    (void)hipFree(d.slow_tiles);
     (void)hipFree(d.partials);
     d = paro_device_tables();
 }
@@ -621,11 +350,10 @@ int fill_tables(const paro_plan_t *pl, paro_device_tables &d) {
     if ((rc = upload(&d.dtype, pl->dtype.data(), pl->dtype.size()))) return rc;
     if ((rc = upload(&d.no_decay, pl->no_decay.data(), pl->no_decay.size()))) return rc;
     d.tiles_per_chunk = (pl->L + TILE - 1) / TILE;
-    // one partial per block of the largest sweep-1 launch (a launch covers one chunk of L elements),
+    // one partial per block of a sweep-1 launch (a launch covers one chunk of L elements),
     // followed by room for the second-level sums
-    // (the one-wave fold's blocks, then the blocks of a launch over the boundary tiles)
-    int64_t n_part = fold4_grid(pl->L) + (pl->L + TILE - 1) / TILE;
-    if (n_part < PARO_MAX_PARTIALS) n_part = PARO_MAX_PARTIALS;
+    int64_t n_part = piece_grid(pl->L);
+    if (n_part < PARO_MIN_PARTIALS) n_part = PARO_MIN_PARTIALS;
     d.n_partials = n_part;
     const int64_t n_level2 = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
     PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), (n_part + n_level2) * sizeof(double)));
@@ -643,8 +371,6 @@ int ensure_device(paro_plan_t *pl) {
         return PARO_OK;
     }
     paro_device_tables d;
-    PARO_HIP(hipDeviceGetAttribute(&d.n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-    if (d.n_cu < 1) d.n_cu = 256;
     PARO_HIP(hipDeviceGetAttribute(&d.lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev));
     if (d.lds_per_cu < 65536) d.lds_per_cu = 65536;
     const int rc = fill_tables(pl, d);
@@ -657,9 +383,9 @@ int ensure_device(paro_plan_t *pl) {
     return PARO_OK;
 }
 
-// Builds, once, the per-tile table and the per-chunk lists of boundary tiles (for calls that work
-// tensor by tensor: the tensor layout, a weight-decay mask).  Too large a table (more than 4 Mi
-// tiles) is not built; the callers then use the kernels that search.
+// Builds, once, the per-tile table (for calls that work tensor by tensor: the tensor layout, a
+// weight-decay mask).  Too large a table (more than 4 Mi tiles) is not built; the kernels then
+// search the offset table for every block.
 int ensure_tile_table(paro_plan_t *pl) {
     std::lock_guard<std::mutex> lock(pl->dev_mutex);
     paro_device_tables &d = pl->dev;
@@ -667,89 +393,51 @@ int ensure_tile_table(paro_plan_t *pl) {
     d.tile_tab_tried = true;
     if ((int64_t)pl->P * d.tiles_per_chunk > (int64_t)4 << 20) return PARO_OK;
     std::vector<paro_tile_info> tab;
-    std::vector<int32_t> slow;
     try {
         tab.resize((size_t)pl->P * d.tiles_per_chunk);
-        d.slow_start.assign((size_t)pl->P + 1, 0);
-        const int64_t n_nz = (int64_t)pl->nz_tensor.size();
-        for (int c = 0; c < pl->P; ++c) {
-            d.slow_start[c] = (int64_t)slow.size();
-            for (int64_t i = 0; i < d.tiles_per_chunk; ++i) {
-                const int64_t f0 = (int64_t)c * pl->L + i * TILE;
-                const int64_t f1 = std::min(f0 + (int64_t)TILE, (int64_t)(c + 1) * pl->L);   // end of the tile
-                paro_tile_info &ti = tab[(size_t)c * d.tiles_per_chunk + i];
-                ti.toff = 0;
-                ti.tensor = -2;
-                ti.first_seg = (int32_t)n_nz;
-                if (f0 >= pl->total) continue;
-                const int64_t k = std::upper_bound(pl->nz_off.begin(), pl->nz_off.end(), f0) - pl->nz_off.begin() - 1;
-                if (f1 <= pl->nz_off[k + 1]) {
-                    ti.tensor = pl->nz_tensor[k];
-                    ti.toff = f0 - pl->nz_off[k];
-                    ti.first_seg = pl->dtype[ti.tensor];
-                } else {
-                    ti.tensor = -1;
-                    ti.first_seg = (int32_t)k;
-                    slow.push_back((int32_t)i);
-                }
-            }
-        }
-        d.slow_start[pl->P] = (int64_t)slow.size();
     } catch (const std::bad_alloc &) {
         return fail(PARO_ENOMEM, "out of host memory while building the per-tile table");
     }
-    int rc;
-    if ((rc = upload(&d.slow_tiles, slow.data(), slow.size()))) return rc;
-    if ((rc = upload(&d.tile_tab, tab.data(), tab.size()))) {
-        (void)hipFree(d.slow_tiles);
-        d.slow_tiles = nullptr;
-        return rc;
+    const int64_t n_nz = (int64_t)pl->nz_tensor.size();
+    for (int c = 0; c < pl->P; ++c) {
+        for (int64_t i = 0; i < d.tiles_per_chunk; ++i) {
+            const int64_t f0 = (int64_t)c * pl->L + i * TILE;
+            const int64_t f1 = std::min(f0 + (int64_t)TILE, (int64_t)(c + 1) * pl->L);   // end of the tile
+            paro_tile_info &ti = tab[(size_t)c * d.tiles_per_chunk + i];
+            ti.toff = 0;
+            ti.tensor = -2;
+            ti.first_seg = (int32_t)n_nz;
+            if (f0 >= pl->total) continue;
+            const int64_t k = std::upper_bound(pl->nz_off.begin(), pl->nz_off.end(), f0) - pl->nz_off.begin() - 1;
+            if (f1 <= pl->nz_off[k + 1]) {
+                ti.tensor = pl->nz_tensor[k];
+                ti.toff = f0 - pl->nz_off[k];
+                ti.first_seg = pl->dtype[ti.tensor];
+            } else {
+                ti.tensor = -1;
+                ti.first_seg = (int32_t)k;
+            }
+        }
     }
-    return PARO_OK;
+    return upload(&d.tile_tab, tab.data(), tab.size());
 }
 
-// Blocks of a launch over n_tiles tiles, for a kernel that takes tpbk tiles per block.
-int grid_for_tiles(int64_t n_tiles, int tpbk) {
-    const int64_t nb = (n_tiles + tpbk - 1) / tpbk;
-    return (int)(nb < 1 ? 1 : nb);
-}
-int grid_for(int64_t n, int tpbk) { return grid_for_tiles((n + TILE - 1) / TILE, tpbk); }
-
-// Chunk c's part of the per-tile table and of the list of boundary tiles (null / 0 without a table).
-struct ChunkTiles {
-    const paro_tile_info *tab = nullptr;
-    const int32_t *slow = nullptr;
-    int n_slow = 0;
-};
-ChunkTiles chunk_tiles(const paro_plan_t *pl, int64_t c) {
-    ChunkTiles ct;
-    if (!pl->dev.tile_tab) return ct;
-    ct.tab = pl->dev.tile_tab + c * pl->dev.tiles_per_chunk;
-    ct.slow = pl->dev.slow_tiles + pl->dev.slow_start[(size_t)c];
-    ct.n_slow = (int)(pl->dev.slow_start[(size_t)c + 1] - pl->dev.slow_start[(size_t)c]);
-    return ct;
-}
-
-TileSegs segs_for(const paro_plan_t *pl, int64_t range_begin, bool chunk_launch) {
-    TileSegs s;
-    s.s_off = nullptr;
-    s.s_head = nullptr;
-    s.tm.nz_off = pl->dev.nz_off;
-    s.tm.nz_tensor = pl->dev.nz_tensor;
-    s.tm.dtype = pl->dev.dtype;
-    s.tm.no_decay = pl->dev.no_decay;
-    s.tm.n_nz = (int)pl->nz_tensor.size();
-    s.tm.total = pl->total;
-    s.range_begin = range_begin;
-    s.tile_tab = nullptr;
-    s.single_tensor = -1;
-    s.single_toff = 0;
-    s.single_dt = PARO_BF16;
-    // the per-tile table is laid out per chunk: usable when the launch starts on a chunk boundary
-    // and stays inside that chunk
-    if (pl->dev.tile_tab && chunk_launch && range_begin % pl->L == 0)
-        s.tile_tab = pl->dev.tile_tab + (range_begin / pl->L) * pl->dev.tiles_per_chunk;
-    return s;
+// The map from elements to tensors for a launch whose element 0 is flat index `begin`.  The
+// per-tile table is laid out chunk by chunk, so it serves launches that start on a chunk boundary
+// and stay inside that chunk.
+TensorMap map_for(const paro_plan_t *pl, int64_t begin, bool one_chunk) {
+    TensorMap tm;
+    tm.nz_off = pl->dev.nz_off;
+    tm.nz_tensor = pl->dev.nz_tensor;
+    tm.dtype = pl->dev.dtype;
+    tm.no_decay = pl->dev.no_decay;
+    tm.n_nz = (int)pl->nz_tensor.size();
+    tm.total = pl->total;
+    tm.begin = begin;
+    tm.tile_tab = nullptr;
+    if (pl->dev.tile_tab && one_chunk && begin % pl->L == 0)
+        tm.tile_tab = pl->dev.tile_tab + (begin / pl->L) * pl->dev.tiles_per_chunk;
+    return tm;
 }
 
 int check_common(const paro_plan_t *pl, int rank, const char *fn) {
@@ -835,29 +523,17 @@ int launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int gr
                   hipStream_t st) {
     const int64_t n = pl->L;
     double *partials = pl->dev.partials;
-    const int g4 = fold4_grid(n);
-    const unsigned lds = throttle_lds(pl, PARO_FOLD4_WAVES_PER_CU);
+    const unsigned grid = piece_grid(n);
     if (layout == PARO_CHUNK) {
-        PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_reduce4<DT, SUMSQ>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab,
-                                                       pl->P, group_len, n, g, partials));
-        return g4;
+        const unsigned lds = throttle_lds(pl, PARO_FOLD_WAVES_PER_CU);
+        PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_reduce4<DT, SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P,
+                                                       group_len, n, g, partials));
+    } else {
+        const unsigned lds = throttle_lds(pl, PARO_TFOLD_WAVES_PER_CU);
+        hipLaunchKernelGGL((k_reduce4t<SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials,
+                           map_for(pl, c * pl->L, true));
     }
-    TensorLoader ld;
-    ld.dtype = pl->dev.dtype;
-    TileSegs segs = segs_for(pl, c * pl->L, true);
-    const ChunkTiles ct = chunk_tiles(pl, c);
-    if (!ct.tab) {                        // no per-tile table: the searching kernel over every tile
-        const int grid = grid_for(n, PARO_TPBK_FOLD);
-        hipLaunchKernelGGL((k_reduce<TensorLoader, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, g,
-                           partials, segs, nullptr, 0);
-        return grid;
-    }
-    hipLaunchKernelGGL((k_reduce4t<SUMSQ>), dim3(g4), dim3(64), lds, st, tab, pl->P, group_len, n, g, partials, ct.tab);
-    if (ct.n_slow == 0) return g4;
-    const int grid = grid_for_tiles(ct.n_slow, PARO_TPBK_FOLD);
-    hipLaunchKernelGGL((k_reduce<TensorLoader, SUMSQ>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, g,
-                       partials + g4, segs, ct.slow, ct.n_slow);
-    return g4 + grid;
+    return (int)grid;
 }
 
 // Launches the single sweep (no clipping) over chunk c.
@@ -865,39 +541,15 @@ template <bool MASK>
 void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t c, const AdamConsts &a,
                   float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
-    const int g4 = fold4_grid(n);
-    const unsigned lds = throttle_lds(pl, PARO_FUSED4_WAVES_PER_CU);
-    if (layout == PARO_CHUNK && !MASK) {
-        PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_fused4<DT>), dim3(g4), dim3(PARO_FOLD4_TPB), lds, st, tab, pl->P,
-                                                       group_len, n, a, p, m, v, dst));
-        return;
-    }
-    TileSegs segs = segs_for(pl, c * pl->L, true);
-    const ChunkTiles ct = chunk_tiles(pl, c);
-    // the tile-at-a-time kernel: over every tile without a table, else over the boundary tiles
-    const int n_list = ct.tab ? ct.n_slow : 0;
-    const int grid = ct.tab ? grid_for_tiles(ct.n_slow, PARO_TPBK_FOLD) : grid_for(n, PARO_TPBK_FOLD);
-    const uint8_t *no_decay = pl->dev.no_decay;
-    if (layout == PARO_TENSORS) {
-        if (ct.tab)
-            hipLaunchKernelGGL((k_fused4t<true, PARO_BF16, MASK>), dim3(g4), dim3(64), lds, st, tab, pl->P, group_len, n, a, p,
-                               m, v, dst, ct.tab, no_decay);
-        if (ct.tab && n_list == 0) return;
-        TensorLoader ld;
-        ld.dtype = pl->dev.dtype;
-        hipLaunchKernelGGL((k_fused<TensorLoader, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, a,
-                           p, m, v, dst, segs, ct.slow, n_list);
-        return;
-    }
-    if (ct.tab)
-        PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_fused4t<false, DT, MASK>), dim3(g4), dim3(64), lds, st, tab, pl->P,
-                                                       group_len, n, a, p, m, v, dst, ct.tab, no_decay));
-    if (ct.tab && n_list == 0) return;
-    PARO_BY_DTYPE(pl->dtype[0], {
-        ChunkLoader<DT> ld{0};
-        hipLaunchKernelGGL((k_fused<ChunkLoader<DT>, MASK>), dim3(grid), dim3(TPB), 0, st, ld, tab, pl->P, group_len, n, a, p,
-                           m, v, dst, segs, ct.slow, n_list);
-    });
+    const unsigned grid = piece_grid(n);
+    const unsigned lds = throttle_lds(pl, PARO_FUSED_WAVES_PER_CU);
+    const TensorMap tm = map_for(pl, c * pl->L, true);
+    if (layout == PARO_TENSORS)
+        hipLaunchKernelGGL((k_fused4<true, PARO_BF16, MASK>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, a, p, m,
+                           v, dst, tm);
+    else
+        PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_fused4<false, DT, MASK>), dim3(grid), dim3(WAVE), lds, st, tab,
+                                                       pl->P, group_len, n, a, p, m, v, dst, tm));
 }
 
 // Sweep 1 over the whole update range, chunk by chunk; the sum of squares covers
@@ -907,7 +559,7 @@ int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout,
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
     const int own = paro::chunk_of_rank(pl, rank);
-    int n_part = 0;                      // partial sums written by the launches over the rank's own chunk
+    int n_part = 0;                      // partial sums written by the launch over the rank's own chunk
     for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {
         SrcTable tab;
         int gl;
@@ -923,11 +575,12 @@ int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout,
         if (n_part > 2 * FINALIZE_CHUNK) {       // two levels: slices of 2048 partials, then their sums
             const int nb = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
             double *level2 = pl->dev.partials + pl->dev.n_partials;
-            hipLaunchKernelGGL(k_finalize, dim3(nb), dim3(TPB), 0, st, pl->dev.partials, n_part, FINALIZE_CHUNK, level2);
+            hipLaunchKernelGGL(k_finalize, dim3(nb), dim3(FINALIZE_TPB), 0, st, pl->dev.partials, n_part, FINALIZE_CHUNK,
+                               level2);
             PARO_HIP(hipGetLastError());
-            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(TPB), 0, st, level2, nb, nb, sumsq_out);
+            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, level2, nb, nb, sumsq_out);
         } else {
-            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(TPB), 0, st, pl->dev.partials, n_part, n_part, sumsq_out);
+            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, pl->dev.partials, n_part, n_part, sumsq_out);
         }
         PARO_HIP(hipGetLastError());
     }
@@ -939,31 +592,23 @@ int launch_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *gra
                 float *m, float *v, uint16_t *dst, hipStream_t st) {
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
-    const unsigned lds = throttle_lds(pl, PARO_ADAM4_WAVES_PER_CU);
-    if (!pl->any_no_decay) {
-        const int64_t nb = (on / 4 + PARO_ADAM4_TPB - 1) / PARO_ADAM4_TPB;
-        hipLaunchKernelGGL((k_adam4<PACK>), dim3((unsigned)nb), dim3(PARO_ADAM4_TPB), lds, st, a, total_sumsq, grad, p, m, v,
-                           dst, on);
-        PARO_HIP(hipGetLastError());
-        return PARO_OK;
-    }
-    if (!pl->dev.tile_tab) {              // no per-tile table: the searching kernel over the whole range
-        hipLaunchKernelGGL((k_adam<PACK, true>), dim3(grid_for(on, PARO_TPBK_ADAM)), dim3(TPB), 0, st, a, total_sumsq, grad,
-                           p, m, v, dst, on, segs_for(pl, ob, false), nullptr, 0);
+    const unsigned lds = throttle_lds(pl, PARO_ADAM_WAVES_PER_CU);
+    if (!pl->any_no_decay || !pl->dev.tile_tab) {
+        // one launch over the whole range (with a mask but no per-tile table, every block searches)
+        const TensorMap tm = map_for(pl, ob, false);
+        if (pl->any_no_decay)
+            hipLaunchKernelGGL((k_adam4<PACK, true>), dim3(piece_grid(on)), dim3(WAVE), lds, st, a, total_sumsq, grad, p, m, v,
+                               dst, on, tm);
+        else
+            hipLaunchKernelGGL((k_adam4<PACK, false>), dim3(piece_grid(on)), dim3(WAVE), lds, st, a, total_sumsq, grad, p, m, v,
+                               dst, on, tm);
         PARO_HIP(hipGetLastError());
         return PARO_OK;
     }
     for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {      // the table is laid out chunk by chunk
         const int64_t lo = c * pl->L - ob;
-        const ChunkTiles ct = chunk_tiles(pl, c);
-        uint16_t *d = dst ? dst + lo : nullptr;
-        hipLaunchKernelGGL((k_adam4m<PACK>), dim3(fold4_grid(pl->L)), dim3(64), lds, st, a, total_sumsq, grad + lo, p + lo,
-                           m + lo, v + lo, d, pl->L, ct.tab, pl->dev.no_decay);
-        PARO_HIP(hipGetLastError());
-        if (ct.n_slow == 0) continue;
-        hipLaunchKernelGGL((k_adam<PACK, true>), dim3(grid_for_tiles(ct.n_slow, PARO_TPBK_ADAM)), dim3(TPB), 0, st, a,
-                           total_sumsq, grad + lo, p + lo, m + lo, v + lo, d, pl->L, segs_for(pl, c * pl->L, true), ct.slow,
-                           ct.n_slow);
+        hipLaunchKernelGGL((k_adam4<PACK, true>), dim3(piece_grid(pl->L)), dim3(WAVE), lds, st, a, total_sumsq, grad + lo,
+                           p + lo, m + lo, v + lo, dst ? dst + lo : nullptr, pl->L, map_for(pl, c * pl->L, true));
         PARO_HIP(hipGetLastError());
     }
     return PARO_OK;
@@ -1032,8 +677,7 @@ int paro_pack_params(paro_plan_t *pl, int rank, const float *p, uint16_t *dst_ba
     if ((rc = ensure_device(pl))) return rc;
     int64_t dl, so, sl;
     paro_pack_slot(pl, rank, &dl, &so, &sl);
-    const int64_t nb = (sl / 4 + 63) / 64;
-    hipLaunchKernelGGL(k_pack, dim3((unsigned)(nb < 1 ? 1 : nb)), dim3(64), throttle_lds(pl, PARO_COPY_WAVES_PER_CU),
+    hipLaunchKernelGGL(k_pack, dim3(piece_grid(sl)), dim3(WAVE), throttle_lds(pl, PARO_COPY_WAVES_PER_CU),
                        static_cast<hipStream_t>(stream), p, dst_base + so, sl, pl->pack_dtype);
     PARO_HIP(hipGetLastError());
     return PARO_OK;
@@ -1091,11 +735,10 @@ namespace {
 int launch_hop(const paro_plan_t *pl, const void *a, int da, const void *b, int db, float *out, int64_t n,
                hipStream_t st) {
     if (n <= 0) return PARO_OK;
-    const int64_t groups = (n + 3) / 4;
-    const unsigned grid = (unsigned)((groups + 63) / 64);
+    const unsigned grid = piece_grid(n);
     const unsigned lds = throttle_lds(pl, PARO_HOP_WAVES_PER_CU);
 #define PARO_HOP_CASE(A, B)                                                                                   \
-    if (da == A && db == B) hipLaunchKernelGGL((k_hop<A, B>), dim3(grid), dim3(64), lds, st, a, b, out, n)
+    if (da == A && db == B) hipLaunchKernelGGL((k_hop<A, B>), dim3(grid), dim3(WAVE), lds, st, a, b, out, n)
     PARO_HOP_CASE(PARO_BF16, PARO_BF16); PARO_HOP_CASE(PARO_BF16, PARO_F32); PARO_HOP_CASE(PARO_BF16, PARO_F16);
     PARO_HOP_CASE(PARO_F32, PARO_BF16);  PARO_HOP_CASE(PARO_F32, PARO_F32);  PARO_HOP_CASE(PARO_F32, PARO_F16);
     PARO_HOP_CASE(PARO_F16, PARO_BF16);  PARO_HOP_CASE(PARO_F16, PARO_F32);  PARO_HOP_CASE(PARO_F16, PARO_F16);
@@ -1153,9 +796,9 @@ int64_t paro_collective_step(paro_plan_t *pl, int rank, int sched, int collectiv
             const uint16_t *from = static_cast<const uint16_t *>(bufs[m.recv_from]) + m.recv_off;
             uint16_t *mine = static_cast<uint16_t *>(bufs[rank]) + m.recv_off;
             const int64_t n16 = m.recv_len / 8;             // ranges are whole chunks: multiples of 8 elements
-            const unsigned grid = (unsigned)((n16 + 63) / 64);
+            const unsigned grid = (unsigned)((n16 + WAVE - 1) / WAVE);
             if (n16 > 0) {
-                hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(64), throttle_lds(pl, PARO_COPY_WAVES_PER_CU), st,
+                hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(WAVE), throttle_lds(pl, PARO_COPY_WAVES_PER_CU), st,
                                    reinterpret_cast<const u32x4 *>(from), reinterpret_cast<u32x4 *>(mine), n16);
                 PARO_HIP(hipGetLastError());
             }

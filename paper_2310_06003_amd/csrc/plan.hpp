@@ -8,6 +8,8 @@
 
 #include "paro.h"
 
+constexpr int PARO_TILE = 2048;      // elements per tile of the per-tile table
+
 // What a tile (2048 consecutive elements) of a chunk looks like, precomputed so that the kernels do
 // not have to search: tensor >= 0: the whole tile lies inside that tensor, its first element at
 // offset toff, first_seg = the tensor's gradient dtype; tensor == -1: the tile holds a tensor
@@ -21,7 +23,6 @@ struct paro_tile_info {
 
 struct paro_device_tables {
     int device = -1;
-    int n_cu = 0;
     int lds_per_cu = 0;             // bytes of LDS a compute unit has (for the occupancy throttle)
     int64_t *nz_off = nullptr;      // [n_nz + 1] flat start of every non-empty tensor, then Psi
     int32_t *nz_tensor = nullptr;   // [n_nz]     index of that tensor in the caller's list
@@ -31,8 +32,6 @@ struct paro_device_tables {
     bool tile_tab_tried = false;
     paro_tile_info *tile_tab = nullptr;  // [P * tiles_per_chunk], or null when that would be too large
     int64_t tiles_per_chunk = 0;
-    int32_t *slow_tiles = nullptr;       // per chunk, the tiles with tensor == -1 (index inside the chunk)
-    std::vector<int64_t> slow_start;     // [P + 1] where chunk c's list starts in slow_tiles (host copy)
     double *partials = nullptr;     // per-block partial sums of squares, then the second-level sums
     int64_t n_partials = 0;         // capacity of the first level
 };
@@ -59,7 +58,7 @@ struct paro_plan_s {
     paro_device_tables dev;             // filled on the first device call
 };
 
-enum { PARO_MAX_PARTIALS = 4096 };   // smallest partial-sum scratch; also the cap on a persistent grid
+enum { PARO_MIN_PARTIALS = 4096 };   // smallest partial-sum scratch
 
 namespace paro {
 int fail(int code, const std::string &msg);     // records the thread's last error, returns code
