@@ -46,8 +46,12 @@
  * never throws or aborts; paro_last_error() gives the text of the calling
  * thread's last failure.  The caller owns every buffer it passes in.  The
  * library owns the plan: its host tables, and - created on the first device
- * call, on the device that is current then - a few hundred KB of device memory
- * (tensor offset tables and a scratch array of per-block partial sums).  Device
+ * call, on the device that is current then - device memory for the tensor
+ * offset tables and a scratch array of partial sums (8 bytes per 256 elements
+ * of a chunk); the first call that uses the tensor layout or a weight-decay
+ * mask adds a per-tile table (16 bytes per 2048 padded elements, built when it
+ * has at most 4 Mi entries, or at most PARO_TILE_TABLE_MAX_TILES entries when
+ * that environment variable is set; without it the kernels search).  Device
  * functions only enqueue work on `stream` (a hipStream_t passed as void*; NULL =
  * the default stream) and never synchronise; a launch error is reported by the
  * call that launched.  Calls that run concurrently on ONE plan (different
@@ -175,7 +179,10 @@ int paro_pack_slot(const paro_plan_t *plan, int rank, int64_t *dst_len, int64_t 
  *                 the same grad_dtype).
  *   PARO_TENSORS: contrib[q] -> DEVICE array of n_tensors DEVICE pointers, the
  *                 q-th rank's full gradient of each tensor (dtype per tensor as
- *                 planned; each naturally aligned; empty tensors may be NULL).
+ *                 planned; each naturally aligned - 8-byte (2-byte dtypes) or
+ *                 16-byte (fp32) alignment of the data a rank contributes to
+ *                 the range lets the kernels use vector loads, anything less
+ *                 costs element loads; empty tensors may be NULL).
  * grad_out, p, m, v: DEVICE fp32 arrays over the update range, 16-byte aligned.
  * PARO_EALIGN for a misaligned pointer, PARO_EINVAL for a NULL one. */
 

@@ -33,6 +33,7 @@
 #include <algorithm>
 #include <cmath>
 #include <new>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <type_traits>
@@ -384,14 +385,17 @@ int ensure_device(paro_plan_t *pl) {
 }
 
 // Builds, once, the per-tile table (for calls that work tensor by tensor: the tensor layout, a
-// weight-decay mask).  Too large a table (more than 4 Mi tiles) is not built; the kernels then
-// search the offset table for every block.
+// weight-decay mask).  Too large a table (more than 4 Mi tiles, or what the environment variable
+// PARO_TILE_TABLE_MAX_TILES says) is not built; the kernels then search the offset table for every
+// block.
 int ensure_tile_table(paro_plan_t *pl) {
     std::lock_guard<std::mutex> lock(pl->dev_mutex);
     paro_device_tables &d = pl->dev;
     if (d.tile_tab_tried) return PARO_OK;
     d.tile_tab_tried = true;
-    if ((int64_t)pl->P * d.tiles_per_chunk > (int64_t)4 << 20) return PARO_OK;
+    int64_t max_tiles = (int64_t)4 << 20;                   // 64 MB of table
+    if (const char *env = std::getenv("PARO_TILE_TABLE_MAX_TILES")) max_tiles = std::atoll(env);
+    if ((int64_t)pl->P * d.tiles_per_chunk > max_tiles) return PARO_OK;
     std::vector<paro_tile_info> tab;
     try {
         tab.resize((size_t)pl->P * d.tiles_per_chunk);

@@ -258,9 +258,13 @@ def test_runs_are_bit_identical(paro):
     assert outs[0] == outs[1] == outs[2]
 
 
-def test_tensor_layout_small_ragged(paro):
+@pytest.mark.parametrize("table", ["per-tile table", "search"])
+def test_tensor_layout_small_ragged(paro, table, monkeypatch):
     """Tensor layout on a small ragged list: empty and one-element tensors, mixed
-    dtypes, unaligned tensor bases, a weight-decay mask, every rank, 2 steps."""
+    dtypes, unaligned tensor bases, a weight-decay mask, every rank, 2 steps - with
+    the plan's per-tile table and without it (every block searches the offset table)."""
+    if table == "search":
+        monkeypatch.setenv("PARO_TILE_TABLE_MAX_TILES", "0")
     rng = np.random.default_rng(8)
     sizes = [int(s) for s in rng.integers(0, 9, 40)] + [5000, 1, 0, 7, 20000, 3, 2049, 2047, 1, 1, 9000]
     dtypes = [int(x) for x in rng.integers(0, 2, len(sizes))]
@@ -315,9 +319,12 @@ def test_tensor_layout_small_ragged(paro):
 
 
 @pytest.mark.parametrize("P,G,strategy", [(256, 16, "IGG"), (64, 8, "NIG"), (12, 3, "IIG")])
-def test_tensor_layout_many_ranks(paro, P, G, strategy):
+def test_tensor_layout_many_ranks(paro, P, G, strategy, monkeypatch):
     """Tensor layout at large P (the pointer staging covers up to 256 sources), shards of a
-    few tiles that hold both whole-tensor tiles and tiles with boundaries; sampled ranks."""
+    few tiles that hold both whole-tensor tiles and tiles with boundaries; sampled ranks.
+    P = 12 runs without the per-tile table."""
+    if P == 12:
+        monkeypatch.setenv("PARO_TILE_TABLE_MAX_TILES", "0")
     rng = np.random.default_rng(P)
     sizes = [int(s) for s in rng.integers(1, 30, 25)] + [40000, 3, 8192, 2048 * 9, 77, 1_500_000, 123456, 5]
     dtypes = [int(x) for x in rng.choice([wl.BF16, wl.F32, wl.F16], len(sizes))]
