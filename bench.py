@@ -59,7 +59,7 @@ def parse():
 def measured_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs, when a
     summary for this workload has been committed; else None."""
-    path = os.path.join(ROOT, "profiles", f"traffic_k_reduce_{workload}.txt")
+    path = os.path.join(ROOT, "profiles", f"traffic_k_reduce4_{workload}.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -219,7 +219,8 @@ def main():
             "sweep1_fold_sumsq": {"ms": ms1, "bytes_per_param": 2 * P + (4 if clip else 26),
                                   "gbps": bytes_dom / (ms1 * 1e-3) / 1e9},
         },
-        "roofline": {"kernel": "k_reduce (fold + sum of squares)" if clip else "k_fused (fold + Adam + pack)",
+        "roofline": {"kernel": (("k_reduce4t" if args.layout == "tensors" else "k_reduce4") + " (fold + sum of squares)")
+                     if clip else "k_fused4 (fold + Adam + pack)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic},
     }

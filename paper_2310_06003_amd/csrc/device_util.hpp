@@ -31,7 +31,7 @@ namespace {
 #define PARO_FOLD_WAVES_PER_CU 14
 #endif
 #ifndef PARO_TFOLD_WAVES_PER_CU
-#define PARO_TFOLD_WAVES_PER_CU 16  // tensor layout: two more dependent look-ups per wave to hide
+#define PARO_TFOLD_WAVES_PER_CU 14  // the same fold out of per-tensor gradients
 #endif
 #ifndef PARO_FUSED_WAVES_PER_CU
 #define PARO_FUSED_WAVES_PER_CU 10
