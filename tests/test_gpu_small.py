@@ -173,10 +173,12 @@ def test_fp32_contributions_chunk_layout(paro):
 
 
 @pytest.mark.parametrize("P,G,total", [(1, 1, 1), (1, 1, 4099), (4, 2, 1), (4, 4, 3), (8, 2, 8 * 8 * 300 - 1),
-                                        (64, 8, 64 * 2048 + 8), (256, 16, 256 * 24)])
+                                        (64, 8, 64 * 2048 + 8), (256, 16, 256 * 24), (2, 2, 2 * 256),
+                                        (2, 1, 2 * 264 - 5)])
 def test_layout_edge_cases(paro, P, G, total):
     """One element (a shard that is almost all padding), P = 1, a ragged last tile,
-    a shard of exactly one tile plus 8, the largest supported P."""
+    a shard of exactly one tile plus 8, the largest supported P, a shard of exactly one
+    block of 256 elements, one block plus 8 with a ragged end."""
     lay = orc.layout(P, G, [total])
     n = P * lay.L
     dev, host = _flat_inputs(P, n, seed=31)
