@@ -13,14 +13,17 @@
 namespace {
 
 // Cache-policy and occupancy knobs (the defaults are the measured best on MI355X).
-#ifndef PARO_NT_FOLD
-#define PARO_NT_FOLD 1              // streaming (non-temporal) loads for the contributions
+// Everything is touched once: loads are streaming (nt) loads.  Cache policy of the stores, as the
+// instruction's bits: 1 = sc0, 2 = nt, 16 = sc1 (0 = default policy): streaming at system scope
+// (nt sc1), which the mixed read/write sweeps like 2 % better than nt alone.
+#ifndef PARO_POL_G_ST
+#define PARO_POL_G_ST 18            // the reduced gradient out of sweep 1
 #endif
-#ifndef PARO_NT_GSTORE
-#define PARO_NT_GSTORE 1            // streaming stores of the reduced gradient in sweep 1
+#ifndef PARO_POL_STATE_ST
+#define PARO_POL_STATE_ST 18        // p, m, v and the packed parameters out of them
 #endif
-#ifndef PARO_NT_STATE
-#define PARO_NT_STATE 3             // g, p, m, v in the Adam sweeps: bit 0 streaming loads, bit 1 streaming stores
+#ifndef PARO_POL_LIGHT_ST
+#define PARO_POL_LIGHT_ST 18
 #endif
 #ifndef PARO_BATCH
 #define PARO_BATCH 16               // contributions loaded before the first is consumed
@@ -123,24 +126,31 @@ template <class V>
 __device__ __forceinline__ const __attribute__((address_space(1))) V *global_ptr(uintptr_t a) {
     return reinterpret_cast<const __attribute__((address_space(1))) V *>(a);
 }
-template <bool NT, class V>
-__device__ __forceinline__ V ld_as(const __attribute__((address_space(1))) V *p) {
-    if (NT) return __builtin_nontemporal_load(p);
-    return *p;
+// Streaming (non-temporal) load of something read once.
+template <class V>
+__device__ __forceinline__ V ld_nt(const V *p) { return __builtin_nontemporal_load(p); }
+template <class V>
+__device__ __forceinline__ V ld_nt(const __attribute__((address_space(1))) V *p) { return __builtin_nontemporal_load(p); }
+
+// ---- stores through per-wave buffer descriptors.  A block's stores to one array go through a
+// descriptor that covers exactly the block's piece of it (a wave-uniform base address and a byte
+// count): the instruction then carries its cache policy as an immediate - which a plain store
+// cannot express beyond "non-temporal" - and the hardware drops whatever falls outside the piece.
+// (Loads stay plain streaming loads: building a descriptor per contribution cost the fold 5 %.)
+typedef __amdgpu_buffer_rsrc_t wave_buf;
+__device__ __forceinline__ wave_buf wave_buffer(const void *base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
-template <bool NT, class V>
-__device__ __forceinline__ V ld_as(const V *p) {
-    if (NT) return __builtin_nontemporal_load(p);
-    return *p;
+template <int POL>
+__device__ __forceinline__ void buf_store8(u32x2 v, wave_buf b, unsigned off) {
+    __builtin_amdgcn_raw_buffer_store_b64(v, b, (int)off, 0, POL);
 }
-template <class Ptr>
-__device__ __forceinline__ auto ld_contrib(Ptr p) { return ld_as<PARO_NT_FOLD != 0>(p); }
-template <bool NT, class V>
-__device__ __forceinline__ void st_as(V *p, V v) {
-    if (NT)
-        __builtin_nontemporal_store(v, p);
-    else
-        *p = v;
+template <int POL>
+__device__ __forceinline__ void buf_store16(u32x4 v, wave_buf b, unsigned off) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, b, (int)off, 0, POL);
+}
+__device__ __forceinline__ u32x4 as_u32x4(float a, float b, float c, float d) {
+    return u32x4{__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
 }
 
 // A value that is the same in every lane, marked as such for the compiler (scalar registers,

@@ -81,32 +81,38 @@ __device__ __forceinline__ void adam1(const AdamConsts &a, float sc, bool decays
     }
 }
 
-constexpr bool STATE_LNT = (PARO_NT_STATE & 1) != 0, STATE_SNT = (PARO_NT_STATE & 2) != 0;
+struct State4 { u32x4 p, m, v; };
 
-struct State4 { f32x4 p, m, v; };
+// elements of the block at e0 that lie inside a launch of n elements
+__device__ __forceinline__ unsigned piece_elems(int64_t e0, int64_t n) {
+    return (unsigned)min((int64_t)PIECE, n - e0);
+}
 
 __device__ __forceinline__ State4 load_state4(const float *p, const float *m, const float *v, int64_t e) {
     State4 s;
-    s.p = ld_as<STATE_LNT>(reinterpret_cast<const f32x4 *>(p + e));
-    s.m = ld_as<STATE_LNT>(reinterpret_cast<const f32x4 *>(m + e));
-    s.v = ld_as<STATE_LNT>(reinterpret_cast<const f32x4 *>(v + e));
+    s.p = ld_nt(reinterpret_cast<const u32x4 *>(p + e));
+    s.m = ld_nt(reinterpret_cast<const u32x4 *>(m + e));
+    s.v = ld_nt(reinterpret_cast<const u32x4 *>(v + e));
     return s;
 }
 
 // Adam on the thread's 4 elements; state and (optionally) the low-precision copy written back.
 template <bool PACK>
 __device__ __forceinline__ void update4(const AdamConsts &a, float sc, const bool decays[4], const float gg[4],
-                                        const State4 &s, float *p, float *m, float *v, uint16_t *dst, int64_t e) {
-    float pp[4] = {s.p.x, s.p.y, s.p.z, s.p.w}, mm[4] = {s.m.x, s.m.y, s.m.z, s.m.w},
-          vv[4] = {s.v.x, s.v.y, s.v.z, s.v.w};
+                                        const State4 &s, float *p, float *m, float *v, uint16_t *dst, int64_t e0,
+                                        unsigned elems) {
+    float pp[4] = {__uint_as_float(s.p.x), __uint_as_float(s.p.y), __uint_as_float(s.p.z), __uint_as_float(s.p.w)},
+          mm[4] = {__uint_as_float(s.m.x), __uint_as_float(s.m.y), __uint_as_float(s.m.z), __uint_as_float(s.m.w)},
+          vv[4] = {__uint_as_float(s.v.x), __uint_as_float(s.v.y), __uint_as_float(s.v.z), __uint_as_float(s.v.w)};
 #pragma unroll
     for (int i = 0; i < 4; ++i) adam1(a, sc, decays[i], gg[i], pp[i], mm[i], vv[i]);
-    st_as<STATE_SNT>(reinterpret_cast<f32x4 *>(p + e), f32x4{pp[0], pp[1], pp[2], pp[3]});
-    st_as<STATE_SNT>(reinterpret_cast<f32x4 *>(m + e), f32x4{mm[0], mm[1], mm[2], mm[3]});
-    st_as<STATE_SNT>(reinterpret_cast<f32x4 *>(v + e), f32x4{vv[0], vv[1], vv[2], vv[3]});
+    constexpr int ST = PARO_POL_STATE_ST;
+    buf_store16<ST>(as_u32x4(pp[0], pp[1], pp[2], pp[3]), wave_buffer(p + e0, elems * 4), threadIdx.x * 16);
+    buf_store16<ST>(as_u32x4(mm[0], mm[1], mm[2], mm[3]), wave_buffer(m + e0, elems * 4), threadIdx.x * 16);
+    buf_store16<ST>(as_u32x4(vv[0], vv[1], vv[2], vv[3]), wave_buffer(v + e0, elems * 4), threadIdx.x * 16);
     if (PACK) {
         const u32x2 w = {pack2_lowp(pp[0], pp[1], a.pack_dtype), pack2_lowp(pp[2], pp[3], a.pack_dtype)};
-        st_as<STATE_SNT>(reinterpret_cast<u32x2 *>(dst + e), w);
+        buf_store8<ST>(w, wave_buffer(dst + e0, elems * 2), threadIdx.x * 8);
     }
 }
 
@@ -137,17 +143,23 @@ __device__ __forceinline__ double sumsq4(const float X[4]) {
 }
 
 // --------------------------------------------------------------------- kernels
+
+__device__ __forceinline__ void store_g4(float *g, int64_t e0, unsigned elems, const float X[4]) {
+    buf_store16<PARO_POL_G_ST>(as_u32x4(X[0], X[1], X[2], X[3]), wave_buffer(g + e0, elems * 4), threadIdx.x * 16);
+}
+
 // Sweep 1, chunk layout: g = fold of the contributions; optional per-block partial of sum g^2.
 template <int DT, bool SUMSQ>
 __global__ __launch_bounds__(WAVE) void k_reduce4(const SrcTable src, int P, int group_len, int64_t n,
                                                   float *__restrict__ g, double *__restrict__ partials) {
-    const int64_t e = block_first() + threadIdx.x * EPT;
+    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
     double acc = 0.0;
     if (e < n) {
+        const unsigned elems = piece_elems(e0, n);
         Chunk4Loader<DT> ld{e};
         float X[4];
         fold4(ld, src, P, group_len, X);
-        st_as<PARO_NT_GSTORE != 0>(reinterpret_cast<f32x4 *>(g + e), f32x4{X[0], X[1], X[2], X[3]});
+        store_g4(g, e0, elems, X);
         if (SUMSQ) acc = sumsq4(X);
     }
     if (SUMSQ) {
@@ -166,9 +178,10 @@ __global__ __launch_bounds__(WAVE) void k_reduce4t(const SrcTable src, int P, in
     if (e0 < n) {                                            // wave-uniform
         const Piece pc = piece_of(tm, e0, n);
         if (e < n) {
+            const unsigned elems = piece_elems(e0, n);
             float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};           // padding: the sum of zeros
             if (pc.tensor != -2) fold_tensors(tm, pc, e, src, P, group_len, X);
-            st_as<PARO_NT_GSTORE != 0>(reinterpret_cast<f32x4 *>(g + e), f32x4{X[0], X[1], X[2], X[3]});
+            store_g4(g, e0, elems, X);
             if (SUMSQ) acc = sumsq4(X);
         }
     }
@@ -212,11 +225,12 @@ __global__ __launch_bounds__(WAVE) void k_adam4(const AdamConsts a, const double
     Piece pc;
     if (MASK) pc = piece_of(tm, e0, n);
     if (e >= n) return;
-    const f32x4 G = ld_as<STATE_LNT>(reinterpret_cast<const f32x4 *>(g + e));
+    const unsigned elems = piece_elems(e0, n);
+    const u32x4 G = ld_nt(reinterpret_cast<const u32x4 *>(g + e));
     const State4 s = load_state4(p, m, v, e);
     if (MASK) decay_flags(tm, pc, e, decays);
-    const float gg[4] = {G.x, G.y, G.z, G.w};
-    update4<PACK>(a, sc, decays, gg, s, p, m, v, dst, e);
+    const float gg[4] = {__uint_as_float(G.x), __uint_as_float(G.y), __uint_as_float(G.z), __uint_as_float(G.w)};
+    update4<PACK>(a, sc, decays, gg, s, p, m, v, dst, e0, elems);
 }
 
 // Single sweep when nothing has to wait for the norm (no clipping): fold, Adam and pack; the
@@ -232,6 +246,7 @@ __global__ __launch_bounds__(WAVE) void k_fused4(const SrcTable src, int P, int 
     Piece pc;
     if (TENSORS || MASK) pc = piece_of(tm, e0, n);
     if (e >= n) return;
+    const unsigned elems = piece_elems(e0, n);
     const State4 s = load_state4(p, m, v, e);
     float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if constexpr (TENSORS) {
@@ -242,28 +257,29 @@ __global__ __launch_bounds__(WAVE) void k_fused4(const SrcTable src, int P, int 
     }
     bool decays[4] = {true, true, true, true};
     if (MASK) decay_flags(tm, pc, e, decays);
-    update4<true>(a, a.grad_scale, decays, X, s, p, m, v, dst, e);
+    update4<true>(a, a.grad_scale, decays, X, s, p, m, v, dst, e0, elems);
 }
 
 // Low-precision pack alone.
 __global__ __launch_bounds__(WAVE) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n,
                                                int pack_dtype) {
-    const int64_t e = block_first() + threadIdx.x * EPT;
+    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
     if (e >= n) return;
-    const f32x4 P = ld_as<true>(reinterpret_cast<const f32x4 *>(p + e));
-    const u32x2 w = {pack2_lowp(P.x, P.y, pack_dtype), pack2_lowp(P.z, P.w, pack_dtype)};
-    st_as<true>(reinterpret_cast<u32x2 *>(dst + e), w);
+    const unsigned elems = piece_elems(e0, n);
+    const u32x4 P = ld_nt(reinterpret_cast<const u32x4 *>(p + e));
+    const u32x2 w = {pack2_lowp(__uint_as_float(P.x), __uint_as_float(P.y), pack_dtype),
+                     pack2_lowp(__uint_as_float(P.z), __uint_as_float(P.w), pack_dtype)};
+    buf_store8<PARO_POL_LIGHT_ST>(w, wave_buffer(dst + e0, elems * 2), threadIdx.x * 8);
 }
 
-// One ring hop / one accumulation: out = a + b, element by element in fp32.
+// One ring hop / one accumulation: out = a + b, element by element in fp32.  n may be any
+// length: the descriptors cover the block's whole groups of 4 elements, the thread that holds
+// the last, partial group takes it element by element.
 template <int DT>
 __device__ __forceinline__ void hop_load4(const void *a, int64_t e, float x[4]) {
-    typename Chunk4Loader<DT>::Raw r;
-    if constexpr (DT != PARO_F32)
-        r = ld_as<true>(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(a) + e));
-    else
-        r = ld_as<true>(reinterpret_cast<const u32x4 *>(static_cast<const float *>(a) + e));
-    Chunk4Loader<DT>::to_f32(r, x);
+    constexpr int ESIZE = DT == PARO_F32 ? 4 : 2;
+    using Raw = typename Chunk4Loader<DT>::Raw;
+    Chunk4Loader<DT>::to_f32(ld_nt(reinterpret_cast<const Raw *>(static_cast<const char *>(a) + e * ESIZE)), x);
 }
 template <int DT>
 __device__ __forceinline__ float hop_load1(const void *a, int64_t i) {
@@ -272,21 +288,26 @@ __device__ __forceinline__ float hop_load1(const void *a, int64_t i) {
 
 template <int DA, int DB>
 __global__ __launch_bounds__(WAVE) void k_hop(const void *a, const void *b, float *out, int64_t n) {
-    const int64_t e = block_first() + threadIdx.x * EPT;
+    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    const unsigned whole = piece_elems(e0, n) & ~3u;       // elements of the block in whole groups of 4
     if (e + EPT <= n) {
         float x[4], y[4];
         hop_load4<DA>(a, e, x);
         hop_load4<DB>(b, e, y);
-        st_as<true>(reinterpret_cast<f32x4 *>(out + e), f32x4{x[0] + y[0], x[1] + y[1], x[2] + y[2], x[3] + y[3]});
+        buf_store16<PARO_POL_LIGHT_ST>(as_u32x4(x[0] + y[0], x[1] + y[1], x[2] + y[2], x[3] + y[3]),
+                                       wave_buffer(out + e0, whole * 4), threadIdx.x * 16);
     } else {
-        for (int64_t i = e; i < n; ++i) out[i] = hop_load1<DA>(a, i) + hop_load1<DB>(b, i);   // last, partial group
+        for (int64_t i = e; i < n; ++i) out[i] = hop_load1<DA>(a, i) + hop_load1<DB>(b, i);
     }
 }
 
 // Plain copy of n 16-byte units (an all-gather message landing in the parameter buffer).
 __global__ __launch_bounds__(WAVE) void k_copy16(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * WAVE + threadIdx.x;
-    if (i < n) st_as<true>(dst + i, ld_as<true>(src + i));
+    const int64_t i0 = (int64_t)blockIdx.x * WAVE;
+    if (i0 + threadIdx.x >= n) return;
+    const unsigned bytes = (unsigned)min((int64_t)WAVE, n - i0) * 16;
+    const u32x4 v = ld_nt(src + i0 + threadIdx.x);
+    buf_store16<PARO_POL_LIGHT_ST>(v, wave_buffer(dst + i0, bytes), threadIdx.x * 16);
 }
 
 }  // namespace

@@ -19,13 +19,11 @@ namespace {
 template <int DT>
 struct Chunk4Loader {
     static constexpr int kBatch = PARO_BATCH;
+    static constexpr int ESIZE = DT == PARO_F32 ? 4 : 2;
     using Raw = std::conditional_t<DT == PARO_F32, u32x4, u32x2>;
     int64_t e;                                   // first of the thread's 4 elements
     __device__ __forceinline__ void load(const SrcTable &src, int k, Raw &r) const {
-        if constexpr (DT != PARO_F32)
-            r = ld_contrib(reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(src.p[k]) + e));
-        else
-            r = ld_contrib(reinterpret_cast<const u32x4 *>(static_cast<const float *>(src.p[k]) + e));
+        r = ld_nt(reinterpret_cast<const Raw *>(static_cast<const char *>(src.p[k]) + e * ESIZE));
     }
     static __device__ __forceinline__ void to_f32(const Raw &r, float x[4]) {
         if constexpr (DT != PARO_F32) {
@@ -139,7 +137,7 @@ struct Tensor4Loader {
         const uintptr_t b0 = static_cast<const uintptr_t *>(src.p[k])[tensor] + (uintptr_t)piece_byte_off;
         const uintptr_t mine = b0 + (uintptr_t)threadIdx.x * (4 * ESIZE);
         if ((b0 & (4 * ESIZE - 1)) == 0) {
-            r = ld_contrib(global_ptr<Raw>(mine));
+            r = ld_nt(global_ptr<Raw>(mine));
         } else if constexpr (DT != PARO_F32) {
             const auto *h = global_ptr<uint16_t>(mine);
             r.x = (unsigned)h[0] | ((unsigned)h[1] << 16);
