@@ -52,13 +52,14 @@ class PtrTable:
         return self.table.data_ptr()
 
 
-def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None, hist=None, literal=None, fmt="bf16"):
+def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None, hist=None, literal=None, fmt="bf16",
+                 g_terms=None, v_old=None):
     """gpu / ref: dicts with p, m, v (fp32 numpy) and q (uint16 bf16 bits).  ref is the
     fp64 evaluation (the 1e-6 contract).  literal, when given, is the oracle's all-fp32
     evaluation in the kernel's operation order: IEEE arithmetic leaves no freedom there,
     so it must match bit for bit."""
     tol_p = check_moments_and_params(gpu["p"], gpu["m"], gpu["v"], ref["p"], ref["m"], ref["v"], p_old=p_old,
-                                     m_old=m_old, g_hat=g_hat, what=what, hist=hist)
+                                     m_old=m_old, g_hat=g_hat, what=what, hist=hist, g_terms=g_terms, v_old=v_old)
     check_bf16_within_one_ulp(gpu["q"], ref["q"], what, ref_p=ref["p"], tol_p=tol_p, fmt=fmt)
     if literal is not None:
         for k in ("p", "m", "v", "q"):

@@ -12,16 +12,25 @@ REL = 1e-6
 
 
 def check_moments_and_params(got_p, got_m, got_v, ref_p, ref_m, ref_v, *, p_old, m_old, g_hat,
-                             beta1=0.9, what="", hist=None):
+                             beta1=0.9, beta2=0.999, what="", hist=None, g_terms=None, v_old=None):
     """All arrays fp32 (got_*: path under test; ref_*: fp64 evaluation rounded once);
     g_hat = scaled, clipped gradient as fp64.  In a run of several steps each side
     carries its own state, so a rounding made when the terms were large is still
     there after they have cancelled: pass the same dict as `hist` at every step and
-    the term magnitudes become running maxima over the run."""
+    the term magnitudes become running maxima over the run.
+    g_terms: with classic L2 decay the gradient that enters the moments is itself a sum that
+    may cancel, scale * g + wd * p; pass |scale * g| + |wd * p| (fp64) and the second moment,
+    quadratic in that sum, is judged against the terms too (v_old: its old value, default 0)."""
     b1 = float(np.float32(beta1))
     ref_p64, ref_m64, ref_v64 = (a.astype(np.float64) for a in (ref_p, ref_m, ref_v))
-    floor_m = np.abs(b1 * m_old.astype(np.float64)) + np.abs((1 - b1) * g_hat)
-    tol_v = REL * np.abs(ref_v64)
+    mag_g = np.abs(g_hat) if g_terms is None else np.maximum(np.abs(g_hat), g_terms)
+    floor_m = np.abs(b1 * m_old.astype(np.float64)) + (1 - b1) * mag_g
+    floor_v = np.abs(ref_v64)
+    if g_terms is not None:
+        b2 = float(np.float32(beta2))
+        old = 0.0 if v_old is None else np.abs(b2 * v_old.astype(np.float64))
+        floor_v = np.maximum(floor_v, old + (1 - b2) * mag_g * mag_g)
+    tol_v = REL * floor_v
     floor_p = np.abs(p_old.astype(np.float64)) + np.abs(ref_p64 - p_old.astype(np.float64))
     floor_p = np.maximum(np.abs(ref_p64), floor_p)
     floor_m = np.maximum(np.abs(ref_m64), floor_m)

@@ -363,6 +363,88 @@ def test_tensor_layout_many_ranks(paro, P, G, strategy, monkeypatch):
         compare_step(got, ref, p_old=old[0], m_old=old[1], g_hat=g_hat, what=what, literal=lit)
 
 
+def test_chunk_layout_with_decay_mask(paro):
+    """Chunk-layout contributions with a per-tensor weight-decay mask (the tensors only matter
+    for the mask): clipped two-sweep step and unclipped single sweep, L2 and decoupled decay."""
+    P, G, strategy = 4, 2, "IIG"
+    sizes = [3000, 17, 2048, 1, 4096 + 5, 700, 9000]
+    no_decay = [0, 1, 0, 1, 1, 0, 1]
+    lay = orc.layout(P, G, sizes)
+    sched = orc.default_sched(P, G)
+    n = P * lay.L
+    dev, host = _flat_inputs(P, n, seed=81)
+    for t, h in zip(dev, host):
+        t[lay.total:] = 0
+        h[lay.total:] = 0
+    state = [np_of(t) for t in wl.master_state(n, 82)]
+    for a in state:
+        a[lay.total:] = 0
+    pl = paro.paro_plan(P, G, strategy, sizes, no_decay=no_decay)
+    for adamw in (True, False):
+        for max_norm in (0.0, 0.003):
+            hp = dict(hp_dict(P, max_norm=max_norm), adamw=adamw, weight_decay=0.1)
+            for rank in range(P):
+                ob, ol = orc.state_range(lay, rank, strategy[2])
+                contrib = [t[ob:ob + ol] for t in dev]
+                g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, [h[ob:ob + ol] for h in host], "chunk")
+                old = [a[ob:ob + ol].copy() for a in state]
+                ref = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=2,
+                                    no_decay=no_decay)
+                lit = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=2,
+                                    no_decay=no_decay, literal32=True)
+                p, m, v = (torch.from_numpy(a.copy()).to(DEV) for a in old)
+                dst_len, slot_off, slot_len = orc.pack_slot(lay, rank, strategy)
+                dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+                gs = torch.empty(ol, dtype=torch.float32, device=DEV)
+                ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+                paro.paro_step_fused(pl, rank, [c.data_ptr() for c in contrib], paro.PARO_CHUNK,
+                                     hp_struct(paro, hp, 2), gs.data_ptr(), ss.data_ptr(), p.data_ptr(), m.data_ptr(),
+                                     v.data_ptr(), dst.data_ptr(), stream())
+                g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
+                g_terms = None
+                if not adamw:                   # L2: wd * p joins the gradient where the tensor decays
+                    decays = np.ones(ol, bool)
+                    for (t, _toff, soff, ln) in orc.segments(lay, ob, ol):
+                        decays[soff:soff + ln] = not no_decay[t]
+                    wd_p = np.where(decays, float(np.float32(hp["weight_decay"])) * old[0].astype(np.float64), 0.0)
+                    g_terms = np.abs(g_hat) + np.abs(wd_p)
+                    g_hat = g_hat + wd_p
+                got = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=np_of(dst)[slot_off:slot_off + slot_len])
+                compare_step(got, ref, p_old=old[0], m_old=old[1], g_hat=g_hat, g_terms=g_terms, v_old=old[2],
+                             what=f"mask adamw={adamw} clip={max_norm} rank{rank}", literal=lit)
+
+
+def test_tensor_layout_ranks_with_different_alignment(paro):
+    """Per-tensor gradients whose alignment differs from rank to rank: the vector-load / element-load
+    choice is made source by source."""
+    P, G, strategy = 4, 2, "IIG"
+    sizes = [20000, 4096, 30000, 8192]
+    dtypes = [wl.BF16, wl.F32, wl.F16, wl.BF16]
+    lay = orc.layout(P, G, sizes)
+    sched = orc.default_sched(P, G)
+    pl = paro.paro_plan(P, G, strategy, sizes, grad_dtype=dtypes)
+    aligned = wl.tensor_contribs(P, sizes, dtypes, 90, 1, device=DEV, align_elems=128)
+    skewed = wl.tensor_contribs(P, [s + 1 for s in sizes], dtypes, 90, 1, device=DEV, align_elems=1)
+    per_rank = []
+    for q in range(P):
+        if q % 2 == 0:
+            per_rank.append(aligned[q].tensors)
+        else:                                   # every tensor starts one element into its (longer) twin
+            per_rank.append([t[1:] for t in skewed[q].tensors])
+    tables = [PtrTable(ts) for ts in per_rank]
+    host = [[np_of(t) for t in ts] for ts in per_rank]
+    assert any(t.data_ptr() % 8 for t in per_rank[1]) and not any(t.data_ptr() % 16 for t in per_rank[0])
+    for rank in range(P):
+        ob, ol = orc.state_range(lay, rank, strategy[2])
+        g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, host, "tensors")
+        g = torch.empty(ol, dtype=torch.float32, device=DEV)
+        ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+        paro.paro_reduce_shard(pl, rank, [t.ptr() for t in tables], paro.PARO_TENSORS, g.data_ptr(), ss.data_ptr(),
+                               stream())
+        assert np_of(g).tobytes() == g_ref.tobytes(), f"rank {rank}"
+        assert abs(float(ss.item()) - ss_ref) <= 1e-12 * ss_ref
+
+
 def _rng(lay, rank, strategy):
     ob, ol = orc.state_range(lay, rank, strategy[2])
     return ob, ob + ol
