@@ -413,10 +413,12 @@ int ensure_tile_table(paro_plan_t *pl) {
     std::lock_guard<std::mutex> lock(pl->dev_mutex);
     paro_device_tables &d = pl->dev;
     if (d.tile_tab_tried) return PARO_OK;
-    d.tile_tab_tried = true;
     int64_t max_tiles = (int64_t)4 << 20;                   // 64 MB of table
     if (const char *env = std::getenv("PARO_TILE_TABLE_MAX_TILES")) max_tiles = std::atoll(env);
-    if ((int64_t)pl->P * d.tiles_per_chunk > max_tiles) return PARO_OK;
+    if ((int64_t)pl->P * d.tiles_per_chunk > max_tiles) {
+        d.tile_tab_tried = true;            // decided: this plan works without the table
+        return PARO_OK;
+    }
     std::vector<paro_tile_info> tab;
     try {
         tab.resize((size_t)pl->P * d.tiles_per_chunk);
@@ -444,7 +446,14 @@ int ensure_tile_table(paro_plan_t *pl) {
             }
         }
     }
-    return upload(&d.tile_tab, tab.data(), tab.size());
+    const int rc = upload(&d.tile_tab, tab.data(), tab.size());
+    if (rc != PARO_OK) {                    // the next call tries again (and reports again)
+        (void)hipFree(d.tile_tab);
+        d.tile_tab = nullptr;
+        return rc;
+    }
+    d.tile_tab_tried = true;
+    return PARO_OK;
 }
 
 // The map from elements to tensors for a launch whose element 0 is flat index `begin`.  The
