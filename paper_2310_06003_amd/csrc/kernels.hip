@@ -135,6 +135,12 @@ __device__ __forceinline__ void decay_flags(const TensorMap &tm, const Piece &pc
 // elements are all inside the range or all outside.
 __device__ __forceinline__ int64_t block_first() { return (int64_t)blockIdx.x * PIECE; }
 
+// Where a block of sweep 1 puts its partial sum.  Blocks are dealt round-robin to the 8 XCDs, each
+// with an L2 of its own: giving every XCD its own run of slots lets each L2 collect whole lines of
+// partials before writing them back (slot = blockIdx would make every line a patchwork of 8-byte
+// writes from 8 caches).  The grid of such a launch is a multiple of 8.
+__device__ __forceinline__ unsigned partial_slot() { return (blockIdx.x & 7u) * (gridDim.x >> 3) + (blockIdx.x >> 3); }
+
 __device__ __forceinline__ double sumsq4(const float X[4]) {
     double acc = 0.0;
 #pragma unroll
@@ -164,7 +170,7 @@ __global__ __launch_bounds__(WAVE) void k_reduce4(const SrcTable src, int P, int
     }
     if (SUMSQ) {
         const double s = wave_sum(acc);
-        if (threadIdx.x == 0) partials[blockIdx.x] = s;
+        if (threadIdx.x == 0) partials[partial_slot()] = s;
     }
 }
 
@@ -187,7 +193,7 @@ __global__ __launch_bounds__(WAVE) void k_reduce4t(const SrcTable src, int P, in
     }
     if (SUMSQ) {
         const double s = wave_sum(acc);
-        if (threadIdx.x == 0) partials[blockIdx.x] = s;
+        if (threadIdx.x == 0) partials[partial_slot()] = s;
     }
 }
 
@@ -374,7 +380,7 @@ int fill_tables(const paro_plan_t *pl, paro_device_tables &d) {
     d.tiles_per_chunk = (pl->L + TILE - 1) / TILE;
     // one partial per block of a sweep-1 launch (a launch covers one chunk of L elements),
     // followed by room for the second-level sums
-    int64_t n_part = piece_grid(pl->L);
+    int64_t n_part = ((int64_t)piece_grid(pl->L) + 7) & ~(int64_t)7;
     if (n_part < PARO_MIN_PARTIALS) n_part = PARO_MIN_PARTIALS;
     d.n_partials = n_part;
     const int64_t n_level2 = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
@@ -557,7 +563,7 @@ int launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int gr
                   hipStream_t st) {
     const int64_t n = pl->L;
     double *partials = pl->dev.partials;
-    const unsigned grid = piece_grid(n);
+    const unsigned grid = (piece_grid(n) + 7u) & ~7u;       // a multiple of 8: see partial_slot()
     if (layout == PARO_CHUNK) {
         const unsigned lds = throttle_lds(pl, PARO_FOLD_WAVES_PER_CU);
         PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_reduce4<DT, SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P,
