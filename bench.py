@@ -267,7 +267,9 @@ def main():
         pb = torch.ones(2 * L, dtype=torch.bfloat16, device=dev)
         ms_ag = timed(lambda: paro.paro_collective_step(ag, 0, paro.PARO_RING, paro.PARO_AG, 1, 0, 1,
                                                         [pa.data_ptr(), pb.data_ptr()], st))
+        ms_pack = timed(lambda: paro.paro_pack_params(pl, rank, p.data_ptr(), dst.data_ptr(), st))
         out["extras"] = {
+            "pack_alone_f32_to_bf16": {"ms": ms_pack, "bytes_per_param": 6, "gbps": 6 * L / (ms_pack * 1e-3) / 1e9},
             "ring_hop_f32_plus_bf16": {"ms": ms_hop, "bytes_per_param": 10, "gbps": 10 * L / (ms_hop * 1e-3) / 1e9},
             "accumulate_f32_inplace": {"ms": ms_acc, "bytes_per_param": 12, "gbps": 12 * L / (ms_acc * 1e-3) / 1e9},
             "all_gather_landing_copy_bf16": {"ms": ms_ag, "bytes_per_param": 4, "gbps": 4 * L / (ms_ag * 1e-3) / 1e9},
