@@ -28,6 +28,9 @@ namespace {
 #ifndef PARO_BATCH
 #define PARO_BATCH 16               // contributions loaded before the first is consumed
 #endif
+#ifndef PARO_LANE_BATCH
+#define PARO_LANE_BATCH 4          // ... in a block with a tensor boundary inside (element loads)
+#endif
 // One-wave blocks in flight per compute unit (0 = as many as fit).  The mixed read/write sweeps
 // run faster with fewer requests outstanding than the registers would allow.
 #ifndef PARO_FOLD_WAVES_PER_CU

@@ -153,7 +153,7 @@ struct Tensor4Loader {
 // ... and a tensor boundary (or the end of the data) falls inside the block: every element has
 // its own tensor, dtype and offset; element loads.  Padding contributes +0.
 struct Lane4Loader {
-    static constexpr int kBatch = 4;
+    static constexpr int kBatch = PARO_LANE_BATCH;
     struct Raw { unsigned int bits[4]; };
     int tens[4];
     int dt[4];
