@@ -32,18 +32,21 @@ namespace {
 #define PARO_LANE_BATCH 4          // ... in a block with a tensor boundary inside (element loads)
 #endif
 // One-wave blocks in flight per compute unit (0 = as many as fit).  The mixed read/write sweeps
-// run faster with fewer requests outstanding than the registers would allow.
-#ifndef PARO_FOLD_WAVES_PER_CU
-#define PARO_FOLD_WAVES_PER_CU 14
+// run faster with fewer requests outstanding than the registers would allow.  For the fold the
+// budget is in loads: a wave has min(P, PARO_BATCH) of them in flight, so with P = 16 the numbers
+// below mean 14 waves per compute unit for sweep 1 and 10 for the single sweep (whose waves also
+// load 3 state vectors); with fewer contributions per wave, more waves.
+#ifndef PARO_FOLD_LOADS_PER_CU
+#define PARO_FOLD_LOADS_PER_CU 224
 #endif
-#ifndef PARO_TFOLD_WAVES_PER_CU
-#define PARO_TFOLD_WAVES_PER_CU 14  // the same fold out of per-tensor gradients
-#endif
-#ifndef PARO_FUSED_WAVES_PER_CU
-#define PARO_FUSED_WAVES_PER_CU 10
+#ifndef PARO_FUSED_LOADS_PER_CU
+#define PARO_FUSED_LOADS_PER_CU 190
 #endif
 #ifndef PARO_ADAM_WAVES_PER_CU
 #define PARO_ADAM_WAVES_PER_CU 12
+#endif
+#ifndef PARO_ADAM_MASK_WAVES_PER_CU
+#define PARO_ADAM_MASK_WAVES_PER_CU 16   // with a decay mask: a table look-up per wave to hide as well
 #endif
 #ifndef PARO_HOP_WAVES_PER_CU
 #define PARO_HOP_WAVES_PER_CU 0

@@ -353,6 +353,14 @@ unsigned throttle_lds(const paro_plan_t *pl, int waves_per_cu) {
     return bytes > 65536u ? 65536u : bytes;
 }
 
+// Waves per compute unit that keep about `loads_per_cu` loads in flight when a wave of the fold
+// issues min(P, PARO_BATCH) + extra loads at a time; 0 (no limit) when that is all that fit anyway.
+int fold_waves(int P, int extra, int loads_per_cu) {
+    const int per_wave = std::min(P, PARO_BATCH) + extra;
+    const int waves = loads_per_cu / per_wave;
+    return waves >= 32 ? 0 : std::max(waves, 8);
+}
+
 template <class T>
 int upload(T **dst, const T *src, size_t n) {
     PARO_HIP(hipMalloc(reinterpret_cast<void **>(dst), (n ? n : 1) * sizeof(T)));
@@ -565,11 +573,11 @@ int launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int gr
     double *partials = pl->dev.partials;
     const unsigned grid = (piece_grid(n) + 7u) & ~7u;       // a multiple of 8: see partial_slot()
     if (layout == PARO_CHUNK) {
-        const unsigned lds = throttle_lds(pl, PARO_FOLD_WAVES_PER_CU);
+        const unsigned lds = throttle_lds(pl, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
         PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_reduce4<DT, SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P,
                                                        group_len, n, g, partials));
     } else {
-        const unsigned lds = throttle_lds(pl, PARO_TFOLD_WAVES_PER_CU);
+        const unsigned lds = throttle_lds(pl, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
         hipLaunchKernelGGL((k_reduce4t<SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials,
                            map_for(pl, c * pl->L, true));
     }
@@ -582,7 +590,7 @@ void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int gr
                   float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
     const unsigned grid = piece_grid(n);
-    const unsigned lds = throttle_lds(pl, PARO_FUSED_WAVES_PER_CU);
+    const unsigned lds = throttle_lds(pl, fold_waves(pl->P, 3, PARO_FUSED_LOADS_PER_CU));
     const TensorMap tm = map_for(pl, c * pl->L, true);
     if (layout == PARO_TENSORS)
         hipLaunchKernelGGL((k_fused4<true, PARO_BF16, MASK>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, a, p, m,
@@ -632,7 +640,7 @@ int launch_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *gra
                 float *m, float *v, uint16_t *dst, hipStream_t st) {
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
-    const unsigned lds = throttle_lds(pl, PARO_ADAM_WAVES_PER_CU);
+    const unsigned lds = throttle_lds(pl, pl->any_no_decay ? PARO_ADAM_MASK_WAVES_PER_CU : PARO_ADAM_WAVES_PER_CU);
     if (!pl->any_no_decay || !pl->dev.tile_tab) {
         // one launch over the whole range (with a mask but no per-tile table, every block searches)
         const TensorMap tm = map_for(pl, ob, false);
