@@ -6,19 +6,30 @@ import pytest
 import torch
 
 import workloads as wl
-from harness import DEV, hp_dict, hp_struct, np_of
+from harness import DEV, PtrTable, hp_dict, hp_struct, np_of
 
 pytestmark = pytest.mark.gpu
 
 
+@pytest.mark.parametrize("layout", ["chunk", "tensors with a decay mask"])
 @pytest.mark.parametrize("max_norm", [0.0, 0.01])
-def test_fused_step_replays_from_a_graph(paro, max_norm):
+def test_fused_step_replays_from_a_graph(paro, max_norm, layout):
     P, G, strategy, rank = 8, 4, "IIG", 3
-    sizes = [P * 2048 * 40 + 24]
-    pl = paro.paro_plan(P, G, strategy, sizes)
-    L = paro.paro_shard_len(pl)
-    contrib = wl.chunk_contribs(P, L, 5, device=DEV)
-    ptrs = [t.data_ptr() for t in contrib]
+    if layout == "chunk":
+        sizes = [P * 2048 * 40 + 24]
+        pl = paro.paro_plan(P, G, strategy, sizes)
+        L = paro.paro_shard_len(pl)
+        contrib = wl.chunk_contribs(P, L, 5, device=DEV)
+        ptrs = [t.data_ptr() for t in contrib]
+        kind = paro.PARO_CHUNK
+    else:               # per-tensor gradients, boundaries inside blocks, a mask: the per-tile table is in play
+        sizes = [70000, 3, 2048 * 7, 12345, 1, 300000, 77]
+        pl = paro.paro_plan(P, G, strategy, sizes, grad_dtype=[0, 1, 0, 2, 0, 0, 1], no_decay=[0, 1, 0, 0, 1, 0, 1])
+        L = paro.paro_shard_len(pl)
+        sets = wl.tensor_contribs(P, sizes, [0, 1, 0, 2, 0, 0, 1], 5, 1, device=DEV)
+        tables = [PtrTable(ts.tensors) for ts in sets]
+        ptrs = [t.ptr() for t in tables]
+        kind = paro.PARO_TENSORS
     hp = hp_dict(P, max_norm=max_norm)
     hs = hp_struct(paro, hp, 3)
     dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
@@ -30,7 +41,7 @@ def test_fused_step_replays_from_a_graph(paro, max_norm):
                     ss=torch.zeros(1, dtype=torch.float64, device=DEV))
 
     def step(s, stream):
-        paro.paro_step_fused(pl, rank, ptrs, paro.PARO_CHUNK, hs, s["g"].data_ptr(), s["ss"].data_ptr(),
+        paro.paro_step_fused(pl, rank, ptrs, kind, hs, s["g"].data_ptr(), s["ss"].data_ptr(),
                              s["p"].data_ptr(), s["m"].data_ptr(), s["v"].data_ptr(), s["dst"].data_ptr(), stream)
 
     # eager: three steps in a row, the state after each kept
