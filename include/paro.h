@@ -48,12 +48,13 @@
  * library owns the plan: its host tables, and - created on the first device
  * call, on the device that is current then - device memory for the tensor
  * offset tables and a scratch array of partial sums (8 bytes per 256 elements
- * of a chunk); the first call that uses the tensor layout or a weight-decay
- * mask adds a per-tile table (16 bytes per 2048 padded elements, built when it
- * has at most 4 Mi entries, or at most PARO_TILE_TABLE_MAX_TILES entries when
- * that environment variable is set; without it the kernels search).  Those two
- * first calls allocate and copy synchronously - make them outside any stream
- * capture; every later call only enqueues kernels and can be captured.  Device
+ * of a chunk); the first call for a rank that uses the tensor layout or a
+ * weight-decay mask adds a per-tile table for each chunk of that rank's update
+ * range (16 bytes per 2048 elements, built when the chunk has at most 4 Mi
+ * tiles, or at most PARO_TILE_TABLE_MAX_TILES when that environment variable
+ * is set; without it the kernels search).  Those first calls allocate and copy
+ * synchronously - make them outside any stream capture; every later call only
+ * enqueues kernels and can be captured.  Device
  * functions only enqueue work on `stream` (a hipStream_t passed as void*; NULL =
  * the default stream) and never synchronise; a launch error is reported by the
  * call that launched.  Calls that run concurrently on ONE plan (different

@@ -374,7 +374,7 @@ void free_tables(paro_device_tables &d) {
     (void)hipFree(d.nz_tensor);
     (void)hipFree(d.dtype);
     (void)hipFree(d.no_decay);
-    (void)hipFree(d.tile_tab);
+    for (paro_tile_info *t : d.tile_tab) (void)hipFree(t);
     (void)hipFree(d.partials);
     d = paro_device_tables();
 }
@@ -386,6 +386,8 @@ int fill_tables(const paro_plan_t *pl, paro_device_tables &d) {
     if ((rc = upload(&d.dtype, pl->dtype.data(), pl->dtype.size()))) return rc;
     if ((rc = upload(&d.no_decay, pl->no_decay.data(), pl->no_decay.size()))) return rc;
     d.tiles_per_chunk = (pl->L + TILE - 1) / TILE;
+    d.tile_tab.assign((size_t)pl->P, nullptr);
+    d.tile_tab_tried.assign((size_t)pl->P, 0);
     // one partial per block of a sweep-1 launch (a launch covers one chunk of L elements),
     // followed by room for the second-level sums
     int64_t n_part = ((int64_t)piece_grid(pl->L) + 7) & ~(int64_t)7;
@@ -419,32 +421,34 @@ int ensure_device(paro_plan_t *pl) {
     return PARO_OK;
 }
 
-// Builds, once, the per-tile table (for calls that work tensor by tensor: the tensor layout, a
-// weight-decay mask).  Too large a table (more than 4 Mi tiles, or what the environment variable
-// PARO_TILE_TABLE_MAX_TILES says) is not built; the kernels then search the offset table for every
-// block.
-int ensure_tile_table(paro_plan_t *pl) {
+// Builds, once per chunk, the per-tile tables of the chunks of a rank's update range (for calls
+// that work tensor by tensor: the tensor layout, a weight-decay mask).  Too large a table (more
+// than 4 Mi tiles per chunk, or what the environment variable PARO_TILE_TABLE_MAX_TILES says) is
+// not built; the kernels then search the offset table for every block.
+int ensure_tile_tables(paro_plan_t *pl, int rank) {
     std::lock_guard<std::mutex> lock(pl->dev_mutex);
     paro_device_tables &d = pl->dev;
-    if (d.tile_tab_tried) return PARO_OK;
+    int64_t ob, on;
+    paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
     int64_t max_tiles = (int64_t)4 << 20;                   // 64 MB of table
     if (const char *env = std::getenv("PARO_TILE_TABLE_MAX_TILES")) max_tiles = std::atoll(env);
-    if ((int64_t)pl->P * d.tiles_per_chunk > max_tiles) {
-        d.tile_tab_tried = true;            // decided: this plan works without the table
-        return PARO_OK;
-    }
-    std::vector<paro_tile_info> tab;
-    try {
-        tab.resize((size_t)pl->P * d.tiles_per_chunk);
-    } catch (const std::bad_alloc &) {
-        return fail(PARO_ENOMEM, "out of host memory while building the per-tile table");
-    }
     const int64_t n_nz = (int64_t)pl->nz_tensor.size();
-    for (int c = 0; c < pl->P; ++c) {
+    std::vector<paro_tile_info> tab;
+    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {
+        if (d.tile_tab_tried[(size_t)c]) continue;
+        if (d.tiles_per_chunk > max_tiles) {
+            d.tile_tab_tried[(size_t)c] = 1;         // decided: this chunk works without a table
+            continue;
+        }
+        try {
+            tab.resize((size_t)d.tiles_per_chunk);
+        } catch (const std::bad_alloc &) {
+            return fail(PARO_ENOMEM, "out of host memory while building the per-tile table");
+        }
         for (int64_t i = 0; i < d.tiles_per_chunk; ++i) {
-            const int64_t f0 = (int64_t)c * pl->L + i * TILE;
-            const int64_t f1 = std::min(f0 + (int64_t)TILE, (int64_t)(c + 1) * pl->L);   // end of the tile
-            paro_tile_info &ti = tab[(size_t)c * d.tiles_per_chunk + i];
+            const int64_t f0 = c * pl->L + i * TILE;
+            const int64_t f1 = std::min(f0 + (int64_t)TILE, (c + 1) * pl->L);   // end of the tile
+            paro_tile_info &ti = tab[(size_t)i];
             ti.toff = 0;
             ti.tensor = -2;
             ti.first_seg = (int32_t)n_nz;
@@ -459,20 +463,21 @@ int ensure_tile_table(paro_plan_t *pl) {
                 ti.first_seg = (int32_t)k;
             }
         }
+        paro_tile_info *dev_tab = nullptr;
+        const int rc = upload(&dev_tab, tab.data(), tab.size());
+        if (rc != PARO_OK) {                         // the next call tries again (and reports again)
+            (void)hipFree(dev_tab);
+            return rc;
+        }
+        d.tile_tab[(size_t)c] = dev_tab;
+        d.tile_tab_tried[(size_t)c] = 1;
     }
-    const int rc = upload(&d.tile_tab, tab.data(), tab.size());
-    if (rc != PARO_OK) {                    // the next call tries again (and reports again)
-        (void)hipFree(d.tile_tab);
-        d.tile_tab = nullptr;
-        return rc;
-    }
-    d.tile_tab_tried = true;
     return PARO_OK;
 }
 
 // The map from elements to tensors for a launch whose element 0 is flat index `begin`.  The
-// per-tile table is laid out chunk by chunk, so it serves launches that start on a chunk boundary
-// and stay inside that chunk.
+// per-tile tables are per chunk: they serve launches that start on a chunk boundary and stay
+// inside that chunk.
 TensorMap map_for(const paro_plan_t *pl, int64_t begin, bool one_chunk) {
     TensorMap tm;
     tm.nz_off = pl->dev.nz_off;
@@ -483,8 +488,7 @@ TensorMap map_for(const paro_plan_t *pl, int64_t begin, bool one_chunk) {
     tm.total = pl->total;
     tm.begin = begin;
     tm.tile_tab = nullptr;
-    if (pl->dev.tile_tab && one_chunk && begin % pl->L == 0)
-        tm.tile_tab = pl->dev.tile_tab + (begin / pl->L) * pl->dev.tiles_per_chunk;
+    if (one_chunk && begin % pl->L == 0) tm.tile_tab = pl->dev.tile_tab[(size_t)(begin / pl->L)];
     return tm;
 }
 
@@ -641,19 +645,13 @@ int launch_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *gra
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
     const unsigned lds = throttle_lds(pl, pl->any_no_decay ? PARO_ADAM_MASK_WAVES_PER_CU : PARO_ADAM_WAVES_PER_CU);
-    if (!pl->any_no_decay || !pl->dev.tile_tab) {
-        // one launch over the whole range (with a mask but no per-tile table, every block searches)
-        const TensorMap tm = map_for(pl, ob, false);
-        if (pl->any_no_decay)
-            hipLaunchKernelGGL((k_adam4<PACK, true>), dim3(piece_grid(on)), dim3(WAVE), lds, st, a, total_sumsq, grad, p, m, v,
-                               dst, on, tm);
-        else
-            hipLaunchKernelGGL((k_adam4<PACK, false>), dim3(piece_grid(on)), dim3(WAVE), lds, st, a, total_sumsq, grad, p, m, v,
-                               dst, on, tm);
+    if (!pl->any_no_decay) {
+        hipLaunchKernelGGL((k_adam4<PACK, false>), dim3(piece_grid(on)), dim3(WAVE), lds, st, a, total_sumsq, grad, p, m, v,
+                           dst, on, map_for(pl, ob, false));
         PARO_HIP(hipGetLastError());
         return PARO_OK;
     }
-    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {      // the table is laid out chunk by chunk
+    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {      // chunk by chunk: each has its own per-tile table
         const int64_t lo = c * pl->L - ob;
         hipLaunchKernelGGL((k_adam4<PACK, true>), dim3(piece_grid(pl->L)), dim3(WAVE), lds, st, a, total_sumsq, grad + lo,
                            p + lo, m + lo, v + lo, dst ? dst + lo : nullptr, pl->L, map_for(pl, c * pl->L, true));
@@ -687,7 +685,7 @@ int paro_reduce_shard(paro_plan_t *pl, int rank, const void *const *contrib, int
     if (sumsq_out && (reinterpret_cast<uintptr_t>(sumsq_out) & 7))
         return fail(PARO_EALIGN, "paro_reduce_shard: sumsq_out is not 8-byte aligned");
     if ((rc = ensure_device(pl))) return rc;
-    if (layout == PARO_TENSORS && (rc = ensure_tile_table(pl))) return rc;
+    if (layout == PARO_TENSORS && (rc = ensure_tile_tables(pl, rank))) return rc;
     return do_reduce(pl, rank, contrib, layout, grad_out, sumsq_out, static_cast<hipStream_t>(stream));
 }
 
@@ -707,7 +705,7 @@ int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const floa
     if (dst_base && (reinterpret_cast<uintptr_t>(dst_base) & 15))
         return fail(PARO_EALIGN, "paro_adam_shard: dst_base is not 16-byte aligned");
     if ((rc = ensure_device(pl))) return rc;
-    if (pl->any_no_decay && (rc = ensure_tile_table(pl))) return rc;
+    if (pl->any_no_decay && (rc = ensure_tile_tables(pl, rank))) return rc;
     uint16_t *dst = nullptr;
     if (dst_base) {
         int64_t dl, so, sl;
@@ -751,7 +749,7 @@ int paro_step_fused(paro_plan_t *pl, int rank, const void *const *contrib, int l
             return fail(sumsq_scratch ? PARO_EALIGN : PARO_EINVAL, "paro_step_fused: clipping and skip_nonfinite need sumsq_scratch");
     }
     if ((rc = ensure_device(pl))) return rc;
-    if ((layout == PARO_TENSORS || pl->any_no_decay) && (rc = ensure_tile_table(pl))) return rc;
+    if ((layout == PARO_TENSORS || pl->any_no_decay) && (rc = ensure_tile_tables(pl, rank))) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     int64_t dl, so, sl, ob, on;
     paro_pack_slot(pl, rank, &dl, &so, &sl);

@@ -28,9 +28,10 @@ struct paro_device_tables {
     int32_t *nz_tensor = nullptr;   // [n_nz]     index of that tensor in the caller's list
     uint8_t *dtype = nullptr;       // [T]
     uint8_t *no_decay = nullptr;    // [T]
-    // built at the first call that needs them (tensor layout, weight-decay mask):
-    bool tile_tab_tried = false;
-    paro_tile_info *tile_tab = nullptr;  // [P * tiles_per_chunk], or null when that would be too large
+    // per chunk, built at the first call that works on the chunk tensor by tensor (tensor layout,
+    // weight-decay mask):
+    std::vector<paro_tile_info *> tile_tab;   // [P] the chunk's [tiles_per_chunk] table, or null
+    std::vector<uint8_t> tile_tab_tried;      // [P] the decision for the chunk has been made
     int64_t tiles_per_chunk = 0;
     double *partials = nullptr;     // per-block partial sums of squares, then the second-level sums
     int64_t n_partials = 0;         // capacity of the first level
