@@ -24,6 +24,37 @@ def test_library_exports_every_declared_symbol(paro):
     assert declared == set(paro.EXPORTS)            # the binding covers the same names
 
 
+def test_header_is_plain_c_and_the_host_calls_link_from_c(paro, tmp_path):
+    """The boundary is a C interface: the header compiles as C99, and a C program links against
+    the library and gets the plan's tables (host calls only: no GPU needed)."""
+    import subprocess
+    src = tmp_path / "use_paro.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "paro.h"
+int main(void) {
+    int64_t sizes[3] = {1000, 0, 24};
+    paro_plan_t *pl = 0;
+    if (paro_plan(4, 2, "IIG", sizes, 3, 0, &pl) != PARO_OK) { printf("plan: %s\n", paro_last_error()); return 1; }
+    int64_t b = -1, n = -1;
+    if (paro_range(pl, 3, 'O', &b, &n) != PARO_OK) return 2;
+    printf("%lld %lld %lld %d %d\n", (long long)paro_total(pl), (long long)paro_shard_len(pl), (long long)b,
+           paro_chunk_of_rank(pl, 3), paro_strategy_legal("GNN"));
+    if (paro_plan(4, 3, "IIG", sizes, 3, 0, &pl) != PARO_EINVAL) return 3;
+    paro_plan_destroy(pl);
+    return 0;
+}
+''')
+    exe = tmp_path / "use_paro"
+    libdir = os.path.join(ROOT, "paper_2310_06003_amd")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-o", str(exe), "-L", libdir, "-l:libparo.so", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    lay = orc.layout(4, 2, [1000, 0, 24])
+    ob, _ = orc.state_range(lay, 3, "G")
+    assert [int(x) for x in out] == [lay.total, lay.L, ob, orc.chunk_of_rank(3, 4, 2), 0]
+
+
 def test_strategies(paro):
     import itertools
     for s in ("".join(t) for t in itertools.product("NIG", repeat=3)):
