@@ -92,27 +92,25 @@ def test_llama7b_share_full_size(paro):
     assert not bool(dst[L:].any()), "the other group's slot of the parameter block must stay untouched"
 
 
-def test_llama7b_share_tensor_layout(paro):
-    """The same shard of the 291-tensor Llama-7B list, each simulated rank handing over
-    per-tensor gradients: the fold and the sum of squares against the oracle on every
-    block that holds a tensor boundary plus random ones, then the fused step on samples."""
-    _need_memory(40)
-    P, G, strategy, rank = 16, 8, "IIG", 5
-    sizes = wl.llama7b_sizes()
+def _tensor_layout_at_full_size(paro, sizes, P, G, strategy, rank, L_want, need_gib, seed):
+    """One rank's shard of a model's tensor list, each simulated rank handing over per-tensor
+    gradients: the fold and the sum of squares against the oracle on every block that holds a
+    tensor boundary plus random ones, then the fused step on those samples."""
+    _need_memory(need_gib)
     lay = orc.layout(P, G, sizes)
     L = lay.L
-    assert len(sizes) == 291 and lay.total == 6_738_415_616 and L == 421_150_976
+    assert L == L_want
     sched = orc.default_sched(P, G)
     pl = paro.paro_plan(P, G, strategy, sizes)
     ob, ol = orc.state_range(lay, rank, strategy[2])
     assert paro.paro_range(pl, rank, "O") == (ob, ol) and ol == L
-    sets = wl.tensor_contribs_over_range(P, sizes, ob, ol, 11, device=DEV)
+    sets = wl.tensor_contribs_over_range(P, sizes, ob, ol, seed, device=DEV)
     tables = [PtrTable(s.tensors) for s in sets]
     ptrs = [t.ptr() for t in tables]
     segs = orc.segments(lay, ob, ol)
-    assert len(segs) >= 10                                    # the range crosses many tensors
+    assert len(segs) >= 5                                     # the range crosses several tensors
 
-    p, m, v = wl.master_state(L, 11, device=DEV)
+    p, m, v = wl.master_state(L, seed, device=DEV)
     blk = 1 << 22
     nb = (L + blk - 1) // blk
     rng = np.random.default_rng(3)
@@ -121,6 +119,7 @@ def test_llama7b_share_tensor_layout(paro):
     old = {lo: [np_of(t[lo:lo + n]) for t in (p, m, v)] for lo, n in picks}
 
     dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
+    assert (dst_len, slot_off, slot_len) == orc.pack_slot(lay, rank, strategy)
     dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
     g = torch.empty(L, dtype=torch.float32, device=DEV)
     ss = torch.zeros(1, dtype=torch.float64, device=DEV)
@@ -152,7 +151,22 @@ def test_llama7b_share_tensor_layout(paro):
         got = dict(p=np_of(p[lo:lo + n]), m=np_of(m[lo:lo + n]), v=np_of(v[lo:lo + n]),
                    q=np_of(dst[slot_off + lo:slot_off + lo + n]))
         g_hat = float(np.float32(hp["grad_scale"])) * coef * g_blocks[lo].astype(np.float64)
-        compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"llama7b tensors, block at {lo}", literal=lit)
+        compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"tensor layout, block at {lo}", literal=lit)
+
+
+def test_llama7b_share_tensor_layout(paro):
+    """The 291-tensor Llama-7B list, P = 16, rank 5's shard (20 tensors meet it)."""
+    sizes = wl.llama7b_sizes()
+    assert len(sizes) == 291 and sum(sizes) == 6_738_415_616
+    _tensor_layout_at_full_size(paro, sizes, 16, 8, "IIG", 5, 421_150_976, 40, seed=11)
+
+
+def test_llama65b_share_tensor_layout(paro):
+    """The 723-tensor 65B list, P = 64, rank 21's shard: 64 simulated ranks' per-tensor gradients
+    (about 180 GB), two-level HO-Ring order, a per-tile table for a chunk of half a million tiles."""
+    sizes = wl.llama65b_sizes()
+    assert len(sizes) == 723 and sum(sizes) == 65_285_660_672
+    _tensor_layout_at_full_size(paro, sizes, 64, 8, "IGG", 21, 1_020_088_448, 230, seed=13)
 
 
 def test_llama65b_share_full_size(paro):

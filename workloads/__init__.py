@@ -68,6 +68,10 @@ def llama7b_sizes() -> List[int]:
     return llama_sizes(32, 4096, 11008, 32000)
 
 
+def llama65b_sizes() -> List[int]:
+    return llama_sizes(80, 8192, 22016, 32000)
+
+
 def llama65b_total() -> int:
     return llama_total(80, 8192, 22016, 32000)
 
