@@ -10,7 +10,11 @@ so a block check is exact).
 oracle folds sampled blocks only (the full fold would move 130 GB to the host);
 the sum of squares is checked against an fp64 reduction of the verified
 gradient, and Adam + pack run with a norm total supplied by the harness, as a
-cross-rank sum would supply it."""
+cross-rank sum would supply it.
+
+Both shards again in the tensor layout (the models' tensor lists, every simulated
+rank handing over per-tensor gradients), checked on every block that holds a
+tensor boundary plus random ones."""
 import numpy as np
 import pytest
 import torch
