@@ -1,5 +1,4 @@
 """The cost model of libparo (host only) against the paper's Tables 1-3 and Eq. 1."""
-import itertools
 import os
 
 import pytest

@@ -1,7 +1,6 @@
 """The fused step inside a HIP graph: the device entry points only enqueue kernels on the
 caller's stream (no allocation, no synchronisation, no memset after the plan's first device
 call), so a captured step must replay to the eager result, every time."""
-import numpy as np
 import pytest
 import torch
 
