@@ -410,8 +410,12 @@ int ensure_device(paro_plan_t *pl) {
         return PARO_OK;
     }
     paro_device_tables d;
-    PARO_HIP(hipDeviceGetAttribute(&d.lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev));
-    if (d.lds_per_cu < 65536) d.lds_per_cu = 65536;
+    // LDS per compute unit, for the occupancy throttle; 160 KB on gfx950 if the runtime does not say
+    if (hipDeviceGetAttribute(&d.lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess ||
+        d.lds_per_cu < 65536) {
+        (void)hipGetLastError();
+        d.lds_per_cu = 160 * 1024;
+    }
     const int rc = fill_tables(pl, d);
     if (rc != PARO_OK) {
         free_tables(d);                    // nothing half-built stays behind
