@@ -29,6 +29,9 @@ BLOCK = 1 << 24
 
 
 def _need_memory(gib):
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()                    # what earlier tests left in torch's allocator
     free, _ = torch.cuda.mem_get_info()
     if free < gib * (1 << 30):
         pytest.skip(f"needs {gib} GiB of free device memory")
@@ -170,7 +173,7 @@ def test_llama65b_share_tensor_layout(paro):
     (about 180 GB), two-level HO-Ring order, a per-tile table for a chunk of half a million tiles."""
     sizes = wl.llama65b_sizes()
     assert len(sizes) == 723 and sum(sizes) == 65_285_660_672
-    _tensor_layout_at_full_size(paro, sizes, 64, 8, "IGG", 21, 1_020_088_448, 230, seed=13)
+    _tensor_layout_at_full_size(paro, sizes, 64, 8, "IGG", 21, 1_020_088_448, 210, seed=13)
 
 
 def test_llama65b_share_full_size(paro):
