@@ -52,14 +52,24 @@ class PtrTable:
         return self.table.data_ptr()
 
 
+def l2_terms(hp, step):
+    """What parity.check_moments_and_params needs to propagate an error of the L2-decayed
+    gradient into the parameter: the step's scalars, formed as the contract forms them."""
+    f = np.float32
+    b1, b2 = float(f(hp["beta1"])), float(f(hp["beta2"]))
+    bc1, bc2 = float(f(1.0 - b1 ** step)), float(f(1.0 - b2 ** step))
+    return dict(step_size=float(f(hp["lr"])) / bc1, sqrt_bc2=float(np.sqrt(bc2)), eps=float(f(hp["eps"])))
+
+
 def compare_step(gpu, ref, *, p_old, m_old, g_hat, what, report=None, hist=None, literal=None, fmt="bf16",
-                 g_terms=None, v_old=None):
+                 g_terms=None, v_old=None, l2=None):
     """gpu / ref: dicts with p, m, v (fp32 numpy) and q (uint16 bf16 bits).  ref is the
     fp64 evaluation (the 1e-6 contract).  literal, when given, is the oracle's all-fp32
     evaluation in the kernel's operation order: IEEE arithmetic leaves no freedom there,
     so it must match bit for bit."""
     tol_p = check_moments_and_params(gpu["p"], gpu["m"], gpu["v"], ref["p"], ref["m"], ref["v"], p_old=p_old,
-                                     m_old=m_old, g_hat=g_hat, what=what, hist=hist, g_terms=g_terms, v_old=v_old)
+                                     m_old=m_old, g_hat=g_hat, what=what, hist=hist, g_terms=g_terms, v_old=v_old,
+                                     l2=l2)
     check_bf16_within_one_ulp(gpu["q"], ref["q"], what, ref_p=ref["p"], tol_p=tol_p, fmt=fmt)
     if literal is not None:
         for k in ("p", "m", "v", "q"):

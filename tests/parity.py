@@ -12,7 +12,7 @@ REL = 1e-6
 
 
 def check_moments_and_params(got_p, got_m, got_v, ref_p, ref_m, ref_v, *, p_old, m_old, g_hat,
-                             beta1=0.9, beta2=0.999, what="", hist=None, g_terms=None, v_old=None):
+                             beta1=0.9, beta2=0.999, what="", hist=None, g_terms=None, v_old=None, l2=None):
     """All arrays fp32 (got_*: path under test; ref_*: fp64 evaluation rounded once);
     g_hat = scaled, clipped gradient as fp64.  In a run of several steps each side
     carries its own state, so a rounding made when the terms were large is still
@@ -20,7 +20,10 @@ def check_moments_and_params(got_p, got_m, got_v, ref_p, ref_m, ref_v, *, p_old,
     the term magnitudes become running maxima over the run.
     g_terms: with classic L2 decay the gradient that enters the moments is itself a sum that
     may cancel, scale * g + wd * p; pass |scale * g| + |wd * p| (fp64) and the second moment,
-    quadratic in that sum, is judged against the terms too (v_old: its old value, default 0)."""
+    quadratic in that sum, is judged against the terms too (v_old: its old value, default 0).
+    l2 = dict(step_size, sqrt_bc2, eps): then the parameter's tolerance also carries what an
+    error of 1e-6 * g_terms in that sum does to the step, by first-order propagation through
+    q = m / (sqrt(v) / sqrt_bc2 + eps)."""
     b1 = float(np.float32(beta1))
     ref_p64, ref_m64, ref_v64 = (a.astype(np.float64) for a in (ref_p, ref_m, ref_v))
     mag_g = np.abs(g_hat) if g_terms is None else np.maximum(np.abs(g_hat), g_terms)
@@ -39,6 +42,14 @@ def check_moments_and_params(got_p, got_m, got_v, ref_p, ref_m, ref_v, *, p_old,
         floor_m = hist["m"] = np.maximum(hist.get("m", 0.0), floor_m)
     tol_p = REL * floor_p
     tol_m = REL * floor_m
+    if g_terms is not None and l2 is not None:
+        b2 = float(np.float32(beta2))
+        d_g = REL * mag_g
+        root_v = np.sqrt(np.maximum(ref_v64, 0.0))
+        den = root_v / l2["sqrt_bc2"] + l2["eps"]
+        q = np.abs(ref_m64) / den
+        d_q = d_g * ((1 - b1) / den + q * (1 - b2) * np.abs(g_hat) / (den * l2["sqrt_bc2"] * np.maximum(root_v, 1e-300)))
+        tol_p = tol_p + l2["step_size"] * d_q
     for name, got, ref, tol in (("m", got_m, ref_m64, tol_m), ("v", got_v, ref_v64, tol_v),
                                 ("p", got_p, ref_p64, tol_p)):
         bad = np.abs(got.astype(np.float64) - ref) > tol

@@ -7,7 +7,7 @@ import torch
 
 import oracle as orc
 import workloads as wl
-from harness import DEV, PtrTable, compare_step, hp_dict, hp_struct, np_of, oracle_update, stream
+from harness import DEV, PtrTable, compare_step, hp_dict, hp_struct, l2_terms, np_of, oracle_update, stream
 from parity import ulp_distance_f32
 
 pytestmark = pytest.mark.gpu
@@ -411,7 +411,8 @@ def test_chunk_layout_with_decay_mask(paro):
                     g_hat = g_hat + wd_p
                 got = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=np_of(dst)[slot_off:slot_off + slot_len])
                 compare_step(got, ref, p_old=old[0], m_old=old[1], g_hat=g_hat, g_terms=g_terms, v_old=old[2],
-                             what=f"mask adamw={adamw} clip={max_norm} rank{rank}", literal=lit)
+                             what=f"mask adamw={adamw} clip={max_norm} rank{rank}", literal=lit,
+                             l2=None if adamw else l2_terms(hp, 2))
 
 
 def test_tensor_layout_ranks_with_different_alignment(paro):
