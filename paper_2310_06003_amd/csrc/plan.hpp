@@ -8,7 +8,10 @@
 
 #include "paro.h"
 
-constexpr int PARO_TILE = 2048;      // elements per tile of the per-tile table
+#ifndef PARO_TILE_ELEMS
+#define PARO_TILE_ELEMS 2048
+#endif
+constexpr int PARO_TILE = PARO_TILE_ELEMS;      // elements per tile of the per-tile table (a multiple of 256)
 
 // What a tile (2048 consecutive elements) of a chunk looks like, precomputed so that the kernels do
 // not have to search: tensor >= 0: the whole tile lies inside that tensor, its first element at
