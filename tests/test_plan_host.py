@@ -55,6 +55,14 @@ int main(void) {
     assert [int(x) for x in out] == [lay.total, lay.L, ob, orc.chunk_of_rank(3, 4, 2), 0]
 
 
+def test_bench_refuses_more_than_one_gpu():
+    """This build measures one GPU's share: bench.py says so and exits for any other count."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
+
+
 def test_strategies(paro):
     import itertools
     for s in ("".join(t) for t in itertools.product("NIG", repeat=3)):
