@@ -1,6 +1,7 @@
 """Builds libparo.so (host plan + gfx950 kernels) in-tree with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 
@@ -19,11 +20,31 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp
          "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc")]
 
 
+STAMP = SO + ".srchash"        # hash of what the library in the tree was built from
+
+
+def source_hash() -> str:
+    """sha256 over the compiler flags and the text of every source and header."""
+    h = hashlib.sha256(" ".join(FLAGS[:-2]).encode())          # without the two -I paths (they differ per checkout)
+    for f in SOURCES + HEADERS:
+        h.update(os.path.basename(f).encode())
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def built_hash() -> str:
+    """The source hash recorded when the library in the tree was built ("" if unknown)."""
+    try:
+        with open(STAMP) as fh:
+            return fh.read().strip()
+    except OSError:
+        return ""
+
+
 def stale() -> bool:
-    if not os.path.exists(SO):
-        return True
-    t = os.path.getmtime(SO)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+    """True when there is no library, or it was built from other sources than the tree holds."""
+    return not os.path.exists(SO) or built_hash() != source_hash()
 
 
 def build(verbose: bool = False) -> str:
@@ -31,7 +52,11 @@ def build(verbose: bool = False) -> str:
     cmd = [hipcc] + FLAGS + SOURCES + ["-o", SO]
     if verbose:
         print(" ".join(cmd))
+    if os.path.exists(STAMP):
+        os.remove(STAMP)
     subprocess.run(cmd, check=True)
+    with open(STAMP, "w") as fh:
+        fh.write(source_hash() + "\n")
     return SO
 
 
