@@ -221,6 +221,25 @@ int paro_step_fused(paro_plan_t *plan, int rank, const void *const *contrib, int
                     const paro_adam_t *hp, float *grad_scratch, double *sumsq_scratch, float *p,
                     float *m, float *v, uint16_t *dst_base, void *stream);
 
+/* paro_step_fused for callers that cannot allocate device memory at the call: code
+ * under HIP graph capture whose first call would fall inside the capture, tight
+ * serving or training loops and harnesses that forbid hipMalloc.  Same work, same
+ * results, same buffer arguments as paro_step_fused with layout PARO_CHUNK, but the
+ * per-block partial sums of the norm go to a static device array inside the library
+ * (32 MiB + 16 KiB, held by every GPU the library runs on until the process ends)
+ * instead of the plan's device allocation: this call never allocates or frees
+ * device memory, never synchronises, and does not touch the plan's device tables
+ * (the plan may never have seen a device call).  Limits: chunk layout only; no
+ * weight-decay mask (PARO_EINVAL: it needs the plan's device tables); a chunk of
+ * at most PARO_STATIC_MAX_CHUNK elements (PARO_ERANGE beyond).  All calls on one
+ * GPU share that GPU's array, whatever their plan or stream: calls that overlap in
+ * time on one GPU race on it - serialise them on one stream.  Nothing in the array
+ * has to start at zero (every launch overwrites what it later reads). */
+enum { PARO_STATIC_MAX_CHUNK = 1 << 30 };
+int paro_step_fused_static(const paro_plan_t *plan, int rank, const void *const *contrib,
+                           const paro_adam_t *hp, float *grad_scratch, double *sumsq_scratch, float *p,
+                           float *m, float *v, uint16_t *dst_base, void *stream);
+
 /* ---- the steps around the Update stage: ring hops and scheduled transfers -----
  * One hop of a reduce-scatter ring (Sec. 3.4: each GPU passes the partial sum on
  * to the next one after adding its own contribution), and the same operation as

@@ -28,10 +28,11 @@ PARO_BF16, PARO_F32, PARO_F16 = 0, 1, 2
 PARO_CHUNK, PARO_TENSORS = 0, 1
 PARO_RS, PARO_AG = 0, 1
 PARO_MAX_RANKS = 256
+PARO_STATIC_MAX_CHUNK = 1 << 30
 
 if not os.path.exists(_SO):
     raise ImportError(
-        f"{_SO} is missing: build it first (python -m paper_2310_06003_amd.build, or __graft_entry__.build()). "
+        f"{_SO} is missing: build it first (python paper_2310_06003_amd/build.py, or __graft_entry__.build()). "
         "There is no fallback path.")
 _lib = ctypes.CDLL(_SO)
 
@@ -92,6 +93,8 @@ EXPORTS = {
     "paro_pack_params": (c_int, [c_void_p, c_int, c_void_p, c_void_p, c_void_p]),
     "paro_step_fused": (c_int, [c_void_p, c_int, POINTER(c_void_p), c_int, POINTER(paro_adam_t), c_void_p, c_void_p,
                                 c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
+    "paro_step_fused_static": (c_int, [c_void_p, c_int, POINTER(c_void_p), POINTER(paro_adam_t), c_void_p, c_void_p,
+                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
     "paro_ring_hop": (c_int, [c_void_p, c_void_p, c_int, c_void_p, c_int, c_void_p, c_int64, c_void_p]),
     "paro_collective_step": (c_int64, [c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, POINTER(c_void_p),
                                        c_void_p]),
@@ -241,6 +244,12 @@ def paro_step_fused(plan: Plan, rank: int, contrib: Sequence[int], layout: int, 
                     sumsq_scratch: int, p: int, m: int, v: int, dst_base: int, stream: int = 0) -> None:
     _check(_lib.paro_step_fused(plan.handle, rank, _ptr_array(contrib), layout, byref(hp), grad_scratch,
                                 sumsq_scratch, p, m, v, dst_base, stream))
+
+
+def paro_step_fused_static(plan: Plan, rank: int, contrib: Sequence[int], hp: paro_adam_t, grad_scratch: int,
+                           sumsq_scratch: int, p: int, m: int, v: int, dst_base: int, stream: int = 0) -> None:
+    _check(_lib.paro_step_fused_static(plan.handle, rank, _ptr_array(contrib), byref(hp), grad_scratch,
+                                       sumsq_scratch, p, m, v, dst_base, stream))
 
 
 def paro_ring_hop(plan: Plan, partial_in: int, in_dtype: int, local: int, local_dtype: int, out: int, n: int,

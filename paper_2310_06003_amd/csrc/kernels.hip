@@ -348,9 +348,9 @@ unsigned piece_grid(int64_t n) {
 // faster with 10-14 waves per compute unit in flight than with the 32 the registers would allow
 // (fewer requests fighting over DRAM pages).  The launch asks for dynamic LDS it never touches,
 // sized so that only `waves_per_cu` blocks fit on a compute unit.
-unsigned throttle_lds(const paro_plan_t *pl, int waves_per_cu) {
+unsigned throttle_lds(int lds_per_cu, int waves_per_cu) {
     if (waves_per_cu <= 0) return 0;
-    unsigned bytes = (unsigned)(pl->dev.lds_per_cu / waves_per_cu) / 256u * 256u;
+    unsigned bytes = (unsigned)(lds_per_cu / waves_per_cu) / 256u * 256u;
     return bytes > 65536u ? 65536u : bytes;
 }
 
@@ -360,6 +360,21 @@ int fold_waves(int P, int extra, int loads_per_cu) {
     const int per_wave = std::min(P, PARO_BATCH) + extra;
     const int waves = loads_per_cu / per_wave;
     return waves >= 32 ? 0 : std::max(waves, 8);
+}
+
+// What a launch needs from the device besides the caller's buffers: the LDS size behind the
+// occupancy throttle and the scratch array of partial sums (per-block sums of a sweep-1 launch,
+// then `level2`, the second-level sums).  Either the plan's own allocation or the library's
+// static array.
+struct Scratch {
+    int lds_per_cu;
+    double *partials;
+    double *level2;
+    bool plan_tables;      // the plan's device tables (offset tables, per-tile tables) exist
+};
+
+Scratch plan_scratch(const paro_plan_t *pl) {
+    return Scratch{pl->dev.lds_per_cu, pl->dev.partials, pl->dev.partials + pl->dev.n_partials, true};
 }
 
 template <class T>
@@ -483,8 +498,18 @@ int ensure_tile_tables(paro_plan_t *pl, int rank) {
 // The map from elements to tensors for a launch whose element 0 is flat index `begin`.  The
 // per-tile tables are per chunk: they serve launches that start on a chunk boundary and stay
 // inside that chunk.
-TensorMap map_for(const paro_plan_t *pl, int64_t begin, bool one_chunk) {
+TensorMap map_for(const paro_plan_t *pl, const Scratch &sc, int64_t begin, bool one_chunk) {
     TensorMap tm;
+    if (!sc.plan_tables) {                  // launches that never look at tensors (chunk layout, no decay mask)
+        tm.nz_off = nullptr;
+        tm.nz_tensor = nullptr;
+        tm.dtype = tm.no_decay = nullptr;
+        tm.n_nz = 0;
+        tm.total = pl->total;
+        tm.begin = begin;
+        tm.tile_tab = nullptr;
+        return tm;
+    }
     tm.nz_off = pl->dev.nz_off;
     tm.nz_tensor = pl->dev.nz_tensor;
     tm.dtype = pl->dev.dtype;
@@ -576,31 +601,31 @@ void src_table(const paro_plan_t *pl, int chunk, const void *const *contrib, int
 
 // Launches sweep 1 over chunk c; returns the number of per-block partial sums it writes.
 template <bool SUMSQ>
-int launch_reduce(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t c, float *g,
-                  hipStream_t st) {
+int launch_reduce(const paro_plan_t *pl, const Scratch &sc, int layout, const SrcTable &tab, int group_len, int64_t c,
+                  float *g, hipStream_t st) {
     const int64_t n = pl->L;
-    double *partials = pl->dev.partials;
+    double *partials = sc.partials;
     const unsigned grid = (piece_grid(n) + 7u) & ~7u;       // a multiple of 8: see partial_slot()
     if (layout == PARO_CHUNK) {
-        const unsigned lds = throttle_lds(pl, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
         PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_reduce4<DT, SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P,
                                                        group_len, n, g, partials));
     } else {
-        const unsigned lds = throttle_lds(pl, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
         hipLaunchKernelGGL((k_reduce4t<SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials,
-                           map_for(pl, c * pl->L, true));
+                           map_for(pl, sc, c * pl->L, true));
     }
     return (int)grid;
 }
 
 // Launches the single sweep (no clipping) over chunk c.
 template <bool MASK>
-void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int group_len, int64_t c, const AdamConsts &a,
-                  float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
+void launch_fused(const paro_plan_t *pl, const Scratch &sc, int layout, const SrcTable &tab, int group_len, int64_t c,
+                  const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
     const unsigned grid = piece_grid(n);
-    const unsigned lds = throttle_lds(pl, fold_waves(pl->P, 3, PARO_FUSED_LOADS_PER_CU));
-    const TensorMap tm = map_for(pl, c * pl->L, true);
+    const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 3, PARO_FUSED_LOADS_PER_CU));
+    const TensorMap tm = map_for(pl, sc, c * pl->L, true);
     if (layout == PARO_TENSORS)
         hipLaunchKernelGGL((k_fused4<true, PARO_BF16, MASK>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, a, p, m,
                            v, dst, tm);
@@ -611,8 +636,8 @@ void launch_fused(const paro_plan_t *pl, int layout, const SrcTable &tab, int gr
 
 // Sweep 1 over the whole update range, chunk by chunk; the sum of squares covers
 // the rank's own chunk only.
-int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout, float *grad_out, double *sumsq_out,
-              hipStream_t st) {
+int do_reduce(const paro_plan_t *pl, const Scratch &sc, int rank, const void *const *contrib, int layout, float *grad_out,
+              double *sumsq_out, hipStream_t st) {
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
     const int own = paro::chunk_of_rank(pl, rank);
@@ -623,21 +648,21 @@ int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout,
         const int64_t lo = c * pl->L - ob;
         src_table(pl, (int)c, contrib, layout, lo, &tab, &gl);
         if (c == own && sumsq_out)
-            n_part = launch_reduce<true>(pl, layout, tab, gl, c, grad_out + lo, st);
+            n_part = launch_reduce<true>(pl, sc, layout, tab, gl, c, grad_out + lo, st);
         else
-            launch_reduce<false>(pl, layout, tab, gl, c, grad_out + lo, st);
+            launch_reduce<false>(pl, sc, layout, tab, gl, c, grad_out + lo, st);
         PARO_HIP(hipGetLastError());
     }
     if (sumsq_out) {
         if (n_part > 2 * FINALIZE_CHUNK) {       // two levels: slices of 2048 partials, then their sums
             const int nb = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
-            double *level2 = pl->dev.partials + pl->dev.n_partials;
-            hipLaunchKernelGGL(k_finalize, dim3(nb), dim3(FINALIZE_TPB), 0, st, pl->dev.partials, n_part, FINALIZE_CHUNK,
+            double *level2 = sc.level2;
+            hipLaunchKernelGGL(k_finalize, dim3(nb), dim3(FINALIZE_TPB), 0, st, sc.partials, n_part, FINALIZE_CHUNK,
                                level2);
             PARO_HIP(hipGetLastError());
             hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, level2, nb, nb, sumsq_out);
         } else {
-            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, pl->dev.partials, n_part, n_part, sumsq_out);
+            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, sc.partials, n_part, n_part, sumsq_out);
         }
         PARO_HIP(hipGetLastError());
     }
@@ -645,30 +670,100 @@ int do_reduce(paro_plan_t *pl, int rank, const void *const *contrib, int layout,
 }
 
 template <bool PACK>
-int launch_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, const double *total_sumsq, float *p,
-                float *m, float *v, uint16_t *dst, hipStream_t st) {
+int launch_adam(const paro_plan_t *pl, const Scratch &sc, int rank, const AdamConsts &a, const float *grad,
+                const double *total_sumsq, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
-    const unsigned lds = throttle_lds(pl, pl->any_no_decay ? PARO_ADAM_MASK_WAVES_PER_CU : PARO_ADAM_WAVES_PER_CU);
+    const unsigned lds =
+        throttle_lds(sc.lds_per_cu, pl->any_no_decay ? PARO_ADAM_MASK_WAVES_PER_CU : PARO_ADAM_WAVES_PER_CU);
     if (!pl->any_no_decay) {
         hipLaunchKernelGGL((k_adam4<PACK, false>), dim3(piece_grid(on)), dim3(WAVE), lds, st, a, total_sumsq, grad, p, m, v,
-                           dst, on, map_for(pl, ob, false));
+                           dst, on, map_for(pl, sc, ob, false));
         PARO_HIP(hipGetLastError());
         return PARO_OK;
     }
     for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {      // chunk by chunk: each has its own per-tile table
         const int64_t lo = c * pl->L - ob;
         hipLaunchKernelGGL((k_adam4<PACK, true>), dim3(piece_grid(pl->L)), dim3(WAVE), lds, st, a, total_sumsq, grad + lo,
-                           p + lo, m + lo, v + lo, dst ? dst + lo : nullptr, pl->L, map_for(pl, c * pl->L, true));
+                           p + lo, m + lo, v + lo, dst ? dst + lo : nullptr, pl->L, map_for(pl, sc, c * pl->L, true));
         PARO_HIP(hipGetLastError());
     }
     return PARO_OK;
 }
 
-int do_adam(paro_plan_t *pl, int rank, const AdamConsts &a, const float *grad, const double *total_sumsq, float *p,
-            float *m, float *v, uint16_t *dst /* nullable: no pack */, hipStream_t st) {
-    return dst ? launch_adam<true>(pl, rank, a, grad, total_sumsq, p, m, v, dst, st)
-               : launch_adam<false>(pl, rank, a, grad, total_sumsq, p, m, v, dst, st);
+int do_adam(const paro_plan_t *pl, const Scratch &sc, int rank, const AdamConsts &a, const float *grad,
+            const double *total_sumsq, float *p, float *m, float *v, uint16_t *dst /* nullable: no pack */, hipStream_t st) {
+    return dst ? launch_adam<true>(pl, sc, rank, a, grad, total_sumsq, p, m, v, dst, st)
+               : launch_adam<false>(pl, sc, rank, a, grad, total_sumsq, p, m, v, dst, st);
+}
+
+// The launches of the fused step, arguments already checked: two sweeps when the update waits for
+// the norm (clipping, skip on overflow), else one.
+int launch_step(const paro_plan_t *pl, const Scratch &sc, int rank, const void *const *contrib, int layout,
+                const AdamConsts &a, float *grad_scratch, double *sumsq_scratch, float *p, float *m, float *v,
+                uint16_t *dst_base, hipStream_t st) {
+    int rc;
+    int64_t dl, so, sl, ob, on;
+    paro_pack_slot(pl, rank, &dl, &so, &sl);
+    uint16_t *dst = dst_base + so;
+    if (a.max_norm > 0.0f || a.skip_nonfinite) {
+        if ((rc = do_reduce(pl, sc, rank, contrib, layout, grad_scratch, sumsq_scratch, st))) return rc;
+        return do_adam(pl, sc, rank, a, grad_scratch, sumsq_scratch, p, m, v, dst, st);
+    }
+    paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
+    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {
+        SrcTable tab;
+        int gl;
+        const int64_t lo = c * pl->L - ob;
+        src_table(pl, (int)c, contrib, layout, lo, &tab, &gl);
+        if (pl->any_no_decay)
+            launch_fused<true>(pl, sc, layout, tab, gl, c, a, p + lo, m + lo, v + lo, dst + lo, st);
+        else
+            launch_fused<false>(pl, sc, layout, tab, gl, c, a, p + lo, m + lo, v + lo, dst + lo, st);
+        PARO_HIP(hipGetLastError());
+    }
+    return PARO_OK;
+}
+
+// ---- the library's own scratch, for the entry point that allocates nothing --------------------
+// Partial sums of squares of one sweep-1 launch over a chunk of at most PARO_STATIC_MAX_CHUNK
+// elements (one per block of 256), followed by the second-level sums.  Every device the library
+// runs on holds its own copy of this array, at its own address, until the process ends.
+constexpr int64_t STATIC_PARTIALS = PARO_STATIC_MAX_CHUNK / PIECE;
+constexpr int64_t STATIC_LEVEL2 = (STATIC_PARTIALS + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
+static __device__ __align__(256) double scratch[STATIC_PARTIALS + STATIC_LEVEL2];
+
+constexpr int MAX_DEVICES = 64;
+struct StaticScratch {
+    std::mutex mutex;
+    double *ptr[MAX_DEVICES] = {};       // device address of `scratch` on each device, once asked for
+    int lds_per_cu[MAX_DEVICES] = {};
+};
+StaticScratch g_static;
+
+// The current device's copy of `scratch`.  In host code the array's name is only a handle for the
+// runtime: its device address comes from hipGetSymbolAddress, once per device with that device
+// current, and that address is what kernels, copies and fills get.  Allocates nothing.
+int static_scratch(Scratch *out) {
+    int dev = -1;
+    PARO_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(PARO_EINVAL, "paro_step_fused_static: device index out of range");
+    std::lock_guard<std::mutex> lock(g_static.mutex);
+    if (!g_static.ptr[dev]) {
+        double *ptr = nullptr;
+        PARO_HIP(hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(PARO_EHIP, "hipGetSymbolAddress gave no address for the static scratch array");
+        int lds = 0;
+        if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess ||
+            lds < 65536) {
+            (void)hipGetLastError();
+            lds = 160 * 1024;
+        }
+        g_static.lds_per_cu[dev] = lds;
+        g_static.ptr[dev] = ptr;
+    }
+    *out = Scratch{g_static.lds_per_cu[dev], g_static.ptr[dev], g_static.ptr[dev] + STATIC_PARTIALS, false};
+    return PARO_OK;
 }
 
 }  // namespace
@@ -691,7 +786,7 @@ int paro_reduce_shard(paro_plan_t *pl, int rank, const void *const *contrib, int
         return fail(PARO_EALIGN, "paro_reduce_shard: sumsq_out is not 8-byte aligned");
     if ((rc = ensure_device(pl))) return rc;
     if (layout == PARO_TENSORS && (rc = ensure_tile_tables(pl, rank))) return rc;
-    return do_reduce(pl, rank, contrib, layout, grad_out, sumsq_out, static_cast<hipStream_t>(stream));
+    return do_reduce(pl, plan_scratch(pl), rank, contrib, layout, grad_out, sumsq_out, static_cast<hipStream_t>(stream));
 }
 
 int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const float *grad, const double *total_sumsq,
@@ -717,7 +812,7 @@ int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const floa
         paro_pack_slot(pl, rank, &dl, &so, &sl);
         dst = dst_base + so;
     }
-    return do_adam(pl, rank, a, grad, total_sumsq, p, m, v, dst, static_cast<hipStream_t>(stream));
+    return do_adam(pl, plan_scratch(pl), rank, a, grad, total_sumsq, p, m, v, dst, static_cast<hipStream_t>(stream));
 }
 
 int paro_pack_params(paro_plan_t *pl, int rank, const float *p, uint16_t *dst_base, void *stream) {
@@ -728,7 +823,7 @@ int paro_pack_params(paro_plan_t *pl, int rank, const float *p, uint16_t *dst_ba
     if ((rc = ensure_device(pl))) return rc;
     int64_t dl, so, sl;
     paro_pack_slot(pl, rank, &dl, &so, &sl);
-    hipLaunchKernelGGL(k_pack, dim3(piece_grid(sl)), dim3(WAVE), throttle_lds(pl, PARO_COPY_WAVES_PER_CU),
+    hipLaunchKernelGGL(k_pack, dim3(piece_grid(sl)), dim3(WAVE), throttle_lds(pl->dev.lds_per_cu, PARO_COPY_WAVES_PER_CU),
                        static_cast<hipStream_t>(stream), p, dst_base + so, sl, pl->pack_dtype);
     PARO_HIP(hipGetLastError());
     return PARO_OK;
@@ -755,27 +850,40 @@ int paro_step_fused(paro_plan_t *pl, int rank, const void *const *contrib, int l
     }
     if ((rc = ensure_device(pl))) return rc;
     if ((layout == PARO_TENSORS || pl->any_no_decay) && (rc = ensure_tile_tables(pl, rank))) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    int64_t dl, so, sl, ob, on;
-    paro_pack_slot(pl, rank, &dl, &so, &sl);
-    uint16_t *dst = dst_base + so;
-    if (clip) {
-        if ((rc = do_reduce(pl, rank, contrib, layout, grad_scratch, sumsq_scratch, st))) return rc;
-        return do_adam(pl, rank, a, grad_scratch, sumsq_scratch, p, m, v, dst, st);
+    return launch_step(pl, plan_scratch(pl), rank, contrib, layout, a, grad_scratch, sumsq_scratch, p, m, v, dst_base,
+                       static_cast<hipStream_t>(stream));
+}
+
+int paro_step_fused_static(const paro_plan_t *pl, int rank, const void *const *contrib, const paro_adam_t *hp,
+                           float *grad_scratch, double *sumsq_scratch, float *p, float *m, float *v,
+                           uint16_t *dst_base, void *stream) {
+    const char *fn = "paro_step_fused_static";
+    int rc;
+    AdamConsts a;
+    if ((rc = check_common(pl, rank, fn))) return rc;
+    if (pl->any_no_decay)
+        return fail(PARO_EINVAL, std::string(fn) + ": a weight-decay mask needs the plan's device tables; use paro_step_fused");
+    if (pl->L > PARO_STATIC_MAX_CHUNK)
+        return fail(PARO_ERANGE, std::string(fn) + ": the plan's chunk of " + std::to_string(pl->L) +
+                                     " elements exceeds PARO_STATIC_MAX_CHUNK (" +
+                                     std::to_string((long long)PARO_STATIC_MAX_CHUNK) + ")");
+    if ((rc = check_contrib(pl, contrib, PARO_CHUNK, fn))) return rc;
+    if ((rc = adam_consts(hp, &a, fn))) return rc;
+    if ((rc = check_ptr(p, "paro_step_fused_static: p"))) return rc;
+    if ((rc = check_ptr(m, "paro_step_fused_static: m"))) return rc;
+    if ((rc = check_ptr(v, "paro_step_fused_static: v"))) return rc;
+    if ((rc = check_ptr(dst_base, "paro_step_fused_static: dst_base"))) return rc;
+    a.pack_dtype = pl->pack_dtype;
+    if (a.max_norm > 0.0f || a.skip_nonfinite) {
+        if ((rc = check_ptr(grad_scratch, "paro_step_fused_static: grad_scratch"))) return rc;
+        if (!sumsq_scratch || (reinterpret_cast<uintptr_t>(sumsq_scratch) & 7))
+            return fail(sumsq_scratch ? PARO_EALIGN : PARO_EINVAL,
+                        std::string(fn) + ": clipping and skip_nonfinite need sumsq_scratch");
     }
-    paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
-    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {
-        SrcTable tab;
-        int gl;
-        const int64_t lo = c * pl->L - ob;
-        src_table(pl, (int)c, contrib, layout, lo, &tab, &gl);
-        if (pl->any_no_decay)
-            launch_fused<true>(pl, layout, tab, gl, c, a, p + lo, m + lo, v + lo, dst + lo, st);
-        else
-            launch_fused<false>(pl, layout, tab, gl, c, a, p + lo, m + lo, v + lo, dst + lo, st);
-        PARO_HIP(hipGetLastError());
-    }
-    return PARO_OK;
+    Scratch sc;
+    if ((rc = static_scratch(&sc))) return rc;
+    return launch_step(pl, sc, rank, contrib, PARO_CHUNK, a, grad_scratch, sumsq_scratch, p, m, v, dst_base,
+                       static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"
@@ -787,7 +895,7 @@ int launch_hop(const paro_plan_t *pl, const void *a, int da, const void *b, int 
                hipStream_t st) {
     if (n <= 0) return PARO_OK;
     const unsigned grid = piece_grid(n);
-    const unsigned lds = throttle_lds(pl, PARO_HOP_WAVES_PER_CU);
+    const unsigned lds = throttle_lds(pl->dev.lds_per_cu, PARO_HOP_WAVES_PER_CU);
 #define PARO_HOP_CASE(A, B)                                                                                   \
     if (da == A && db == B) hipLaunchKernelGGL((k_hop<A, B>), dim3(grid), dim3(WAVE), lds, st, a, b, out, n)
     PARO_HOP_CASE(PARO_BF16, PARO_BF16); PARO_HOP_CASE(PARO_BF16, PARO_F32); PARO_HOP_CASE(PARO_BF16, PARO_F16);
@@ -849,7 +957,7 @@ int64_t paro_collective_step(paro_plan_t *pl, int rank, int sched, int collectiv
             const int64_t n16 = m.recv_len / 8;             // ranges are whole chunks: multiples of 8 elements
             const unsigned grid = (unsigned)((n16 + WAVE - 1) / WAVE);
             if (n16 > 0) {
-                hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(WAVE), throttle_lds(pl, PARO_COPY_WAVES_PER_CU), st,
+                hipLaunchKernelGGL(k_copy16, dim3(grid), dim3(WAVE), throttle_lds(pl->dev.lds_per_cu, PARO_COPY_WAVES_PER_CU), st,
                                    reinterpret_cast<const u32x4 *>(from), reinterpret_cast<u32x4 *>(mine), n16);
                 PARO_HIP(hipGetLastError());
             }
