@@ -56,16 +56,25 @@ def parse():
     return ap.parse_args()
 
 
-def measured_traffic(workload: str):
-    """HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs, when a
-    summary for this workload has been committed; else None."""
-    path = os.path.join(ROOT, "profiles", f"traffic_k_reduce4_{workload}.txt")
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (counters cannot be
+    read from inside this process), when a summary for this kernel and workload has been
+    committed under profiles/; returns (bytes or None, where the figure comes from)."""
+    name = f"traffic_{kernel}_{workload}.txt"
+    path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":", 1)[1])
-    return None
+            return float(line.split(":", 1)[1]), f"profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, earlier run)"
+    return None, None
+
+
+def stats(ms):
+    """mean / median / min of per-launch durations in ms."""
+    import numpy as np
+    a = np.asarray(ms, dtype=np.float64)
+    return {"mean": float(a.mean()), "median": float(np.median(a)), "min": float(a.min()), "n": int(a.size)}
 
 
 def main():
@@ -77,8 +86,8 @@ def main():
     import numpy as np
     import torch
 
-    from __graft_entry__ import ensure_built
-    ensure_built()                             # builds libparo.so only if it has never been built
+    from __graft_entry__ import ensure_built, library_identity
+    ensure_built()                             # builds libparo.so if there is none or its sources changed since
     import paper_2310_06003_amd as paro        # raises if there is no library: no fallback path
     import workloads as wl
 
@@ -179,6 +188,7 @@ def main():
     sweep1 = [e[0].elapsed_time(e[1]) for e in events]
     sweep2 = [e[1].elapsed_time(e[2]) for e in events]
     ms1, ms2 = float(np.mean(sweep1)), float(np.mean(sweep2))
+    step_ev = [e[0].elapsed_time(e[2]) for e in events]           # one step on the device, launch gaps included
 
     # the one-call entry point, same work
     torch.cuda.synchronize()
@@ -193,7 +203,8 @@ def main():
     bytes_dom = (2 * P + (4 if clip else 26)) * L
     dom_ms = ms1
     achieved = bytes_dom / (dom_ms * 1e-3) / 1e9
-    traffic = measured_traffic(args.workload) if clip and args.layout == "chunk" else None
+    dom_kernel = ("k_reduce4t" if args.layout == "tensors" else "k_reduce4") if clip else "k_fused4"
+    traffic, traffic_source = measured_traffic(args.workload, dom_kernel) if args.layout == "chunk" else (None, None)
     out = {
         "metric": "shard_params_updated_per_s (fused reduce+Adam+pack step)",
         "value": L / (ms_step * 1e-3),
@@ -215,17 +226,24 @@ def main():
         "hbm_frac_step": bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "algorithmic_bytes_per_param_step": 2 * P + (34 if clip else 26),
         "ms_fused_entry": ms_fused_entry,
+        "ms_per_step_device": stats(step_ev),
+        "library": library_identity(),
         "kernels": {
-            "sweep1_fold_sumsq": {"ms": ms1, "bytes_per_param": 2 * P + (4 if clip else 26),
-                                  "gbps": bytes_dom / (ms1 * 1e-3) / 1e9},
+            "sweep1_fold_sumsq": {"ms": ms1, "ms_stats": stats(sweep1), "bytes_per_param": 2 * P + (4 if clip else 26),
+                                  "gbps": bytes_dom / (ms1 * 1e-3) / 1e9,
+                                  "gbps_median": bytes_dom / (float(np.median(sweep1)) * 1e-3) / 1e9,
+                                  "gbps_best": bytes_dom / (min(sweep1) * 1e-3) / 1e9},
         },
-        "roofline": {"kernel": (("k_reduce4t" if args.layout == "tensors" else "k_reduce4") + " (fold + sum of squares)")
-                     if clip else "k_fused4 (fold + Adam + pack)",
+        "roofline": {"kernel": dom_kernel + (" (fold + sum of squares)" if clip else " (fold + Adam + pack)"),
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic},
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
+                     "launch_ms": stats(sweep1)},
     }
     if clip:
-        out["kernels"]["sweep2_adam_pack"] = {"ms": ms2, "bytes_per_param": 30, "gbps": 30 * L / (ms2 * 1e-3) / 1e9}
+        out["kernels"]["sweep2_adam_pack"] = {"ms": ms2, "ms_stats": stats(sweep2), "bytes_per_param": 30,
+                                              "gbps": 30 * L / (ms2 * 1e-3) / 1e9,
+                                              "gbps_median": 30 * L / (float(np.median(sweep2)) * 1e-3) / 1e9,
+                                              "gbps_best": 30 * L / (min(sweep2) * 1e-3) / 1e9}
 
     def timed(fn, reps=10):
         fn()

@@ -3,11 +3,12 @@
  * AMD MI355X (gfx950).
  *
  * Paper: "Rethinking Memory and Communication Costs for Efficient Large
- * Language Model Training" (PaRO + HO-Ring).  Sec. 3.2 describes the Update
- * stage of PaRO-IGG / IIG / NIG: once the last micro-batch's gradients have
- * been reduce-scattered, each GPU uses its gradient shard to update the
- * optimizer state it keeps and produces low-precision parameters, which an
- * all-gather then distributes.  This library does that per-GPU work:
+ * Language Model Training" (PaRO + HO-Ring).  This library does the per-GPU
+ * work of the Update stage of a PaRO training step (Sec. 3.2, the walk-throughs
+ * of PaRO-IGG / IIG / NIG): after the last micro-batch the reduce-scatter leaves
+ * every rank with the summed gradients of its own shard; the rank runs Adam on
+ * the optimizer state of that shard, and the new parameters leave in 16 bits
+ * for the all-gather that follows.
  *
  *   paro_plan           who owns what (Sec. 3.1.1 sharding states, Table 1
  *                       strategies), in which order the reduce-scatter adds the
@@ -139,17 +140,31 @@ int64_t paro_shard_len(const paro_plan_t *plan);    /* L */
 int64_t paro_padded_total(const paro_plan_t *plan); /* P * L */
 int paro_sched(const paro_plan_t *plan);            /* the resolved schedule kind */
 
-/* chunk owned by a rank under global sharding, and its inverse; < 0 on error */
+/* Chunk owned by a rank under global sharding ('G', Sec. 3.1.1), and its inverse.
+ * With the N GPUs in g groups of M (Sec. 3.4, Fig. 4) rank (group j, local index i)
+ * owns chunk i*g + j: the g chunks of local index i's intra-group shard ('I':
+ * Psi/M elements, Table 2) are dealt to the ranks with that local index, one per
+ * group, so that the inter-group reduce-scatter of PaRO-IIG / NIG and the
+ * inter-group all-gather of PaRO-IGG / IIG (Sec. 3.2) work inside one intra-group
+ * shard.  The figures that would show the assignment are not in the text: this
+ * nesting is the reading taken.  Returns < 0 (an error code) for a rank or chunk
+ * out of range. */
 int paro_chunk_of_rank(const paro_plan_t *plan, int rank);
 int paro_owner_of_chunk(const paro_plan_t *plan, int chunk);
 
-/* range a rank holds of state 'P' (parameters), 'G' (gradients) or 'O'
- * (optimizer state = the update range), in elements of the padded flat buffer */
+/* Range a rank holds of state 'P' (parameters), 'G' (gradients) or 'O'
+ * (optimizer state = the update range), in elements of the padded flat buffer,
+ * from the state's sharding letter (Sec. 3.1.1): 'N' everything, 'I' the rank's
+ * block of g*L elements (Psi/M of Table 2), 'G' its chunk of L (Psi/N).  *len
+ * times the bytes per element is Table 2's entry when P divides Psi.
+ * PARO_ERANGE for a bad rank, PARO_EINVAL for another state letter. */
 int paro_range(const paro_plan_t *plan, int rank, char state, int64_t *begin, int64_t *len);
 
-/* pieces of tensors inside the rank's update range, in order; writes at most
- * cap entries to out (host, may be NULL when cap == 0) and returns the full
- * count, or a negative error */
+/* Pieces of tensors inside the rank's update range, in order (the model state is
+ * sharded as one flat sequence of parameters, Sec. 3.1.1 / Table 2, so a range
+ * cuts through tensors wherever it falls); writes at most cap entries to out
+ * (host, may be NULL when cap == 0) and returns the full count, or a negative
+ * error.  Empty tensors and padding give no piece. */
 int64_t paro_segments(const paro_plan_t *plan, int rank, paro_seg_t *out, int64_t cap);
 
 /* order in which the reduce-scatter adds the P ranks' contributions to a chunk
@@ -168,9 +183,13 @@ int paro_fold_order(const paro_plan_t *plan, int chunk, int32_t *ranks, int32_t 
 int64_t paro_schedule(const paro_plan_t *plan, int rank, int sched, int collective, paro_msg_t *out,
                       int64_t cap);
 
-/* where paro_pack_params writes: the rank's low-precision parameter buffer has
- * *dst_len elements (its 'P' range) and the update range sits at *slot_off in
- * it, *slot_len long */
+/* Where paro_pack_params writes.  The Update stage ends with every rank's new
+ * low-precision parameters being all-gathered into the range its parameter
+ * sharding keeps (Sec. 3.2: across groups for PaRO-IGG / IIG, over all ranks for
+ * PaRO-NIG, not at all when parameters are sharded like the optimizer state): the
+ * rank's parameter buffer has *dst_len elements (its 'P' range) and the update
+ * range sits at *slot_off in it, *slot_len long - the send slot of that
+ * all-gather, in place. */
 int paro_pack_slot(const paro_plan_t *plan, int rank, int64_t *dst_len, int64_t *slot_off,
                    int64_t *slot_len);
 

@@ -8,10 +8,11 @@
  * splits the element range; the operations applied to one element, and their
  * order, do not depend on the thread count.
  *
- * What is computed (paper Sec. 3.2, update stage of PaRO-IGG / IIG / NIG:
- * "each GPU uses its gradient shard to update the optimizer state it keeps and
- * produces low-precision parameters"; Sec. 3.1.2: 2 bytes/param gradients and
- * parameters, 12 bytes/param of Adam state = fp32 master copy + two moments):
+ * What is computed: the per-rank arithmetic of the Update stage of PaRO-IGG /
+ * IIG / NIG (paper Sec. 3.2) - Adam on the rank's own shard from the summed
+ * gradients, new parameters out in 16 bits - with the memory model of Sec. 3.1.2
+ * (2 bytes/param gradients and parameters, 12 bytes/param of Adam state = fp32
+ * master copy + two moments):
  *
  *   fold   g[e]  = sum over the P ranks' contributions, added in the order the
  *                  reduce-scatter ring delivers them (Sec. 3.4), in fp32;

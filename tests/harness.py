@@ -88,3 +88,64 @@ def oracle_update(lay, strategy, rank, g, p, m, v, *, total_sumsq, hp, step, no_
     coef = orc.adam_shard(lay, strategy, rank, g, p, m, v, total_sumsq=total_sumsq, hp=hp, step=step,
                           no_decay=no_decay, literal32=literal32)
     return dict(p=p, m=m, v=v, q=orc.f16_rne(p) if fmt == "f16" else orc.bf16_rne(p), coef=coef)
+
+
+def flat_inputs(P, n, seed, dtype=wl.BF16, integer=False, dist="normal"):
+    dev = wl.chunk_contribs(P, n, seed, dtype=dtype, device=DEV, integer=integer, dist=dist)
+    return dev, [np_of(t) for t in dev]
+
+
+def run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, step, report=None, check_unfused=True):
+    """One rank, chunk layout: reduce, fused step, unfused step; all against the oracle.
+    lay.align must be the plan's alignment."""
+    ob, ol = orc.state_range(lay, rank, strategy[2])
+    contrib = [t[ob:ob + ol] for t in dev]
+    g = torch.empty(ol, dtype=torch.float32, device=DEV)
+    ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+    paro.paro_reduce_shard(pl, rank, [c.data_ptr() for c in contrib], paro.PARO_CHUNK, g.data_ptr(), ss.data_ptr(),
+                           stream())
+    g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, [h[ob:ob + ol] for h in host], "chunk")
+    g_gpu = np_of(g)
+    what = f"{strategy}/sched{sched}/rank{rank}"
+    assert g_gpu.tobytes() == g_ref.tobytes(), what + ": reduced gradient differs"
+    assert abs(float(ss.item()) - ss_ref) <= 1e-12 * ss_ref, what
+
+    p0, m0, v0 = (a[ob:ob + ol].copy() for a in state)
+    total = ss_ref
+    ref = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=step)
+    lit = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=step, literal32=True)
+    g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
+
+    dst_len, slot_off, slot_len = orc.pack_slot(lay, rank, strategy)
+    assert slot_len == ol
+
+    def fresh():
+        return [torch.from_numpy(a.copy()).to(DEV) for a in (p0, m0, v0)]
+
+    # fused
+    p, m, v = fresh()
+    dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+    gs = torch.empty(ol, dtype=torch.float32, device=DEV)
+    ss2 = torch.zeros(1, dtype=torch.float64, device=DEV)
+    paro.paro_step_fused(pl, rank, [c.data_ptr() for c in contrib], paro.PARO_CHUNK, hp_struct(paro, hp, step),
+                         gs.data_ptr(), ss2.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(),
+                         stream())
+    q_all = np_of(dst)
+    fused = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=q_all[slot_off:slot_off + slot_len])
+    compare_step(fused, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=what + " fused", report=report, literal=lit)
+    assert (fused["q"] == orc.bf16_rne(fused["p"])).all(), what + ": pack is not the rounding of the stored p"
+    assert not q_all[:slot_off].any() and not q_all[slot_off + slot_len:].any(), what + ": wrote outside the slot"
+    if hp["max_norm"] > 0:
+        assert np_of(gs).tobytes() == g_ref.tobytes() and abs(float(ss2.item()) - ss_ref) <= 1e-12 * ss_ref
+
+    if check_unfused:
+        p, m, v = fresh()
+        dst2 = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+        tot = torch.tensor([total], dtype=torch.float64, device=DEV)
+        paro.paro_adam_shard(pl, rank, hp_struct(paro, hp, step), g.data_ptr(), tot.data_ptr(), p.data_ptr(),
+                             m.data_ptr(), v.data_ptr(), 0, stream())
+        paro.paro_pack_params(pl, rank, p.data_ptr(), dst2.data_ptr(), stream())
+        for name, t in (("p", p), ("m", m), ("v", v)):
+            assert np_of(t).tobytes() == fused[name].tobytes(), what + f": unfused {name} differs from fused"
+        assert np_of(dst2).tobytes() == q_all.tobytes()
+    return fused, ref

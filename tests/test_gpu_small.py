@@ -7,72 +7,13 @@ import torch
 
 import oracle as orc
 import workloads as wl
-from harness import DEV, PtrTable, compare_step, hp_dict, hp_struct, l2_terms, np_of, oracle_update, stream
+from harness import (DEV, PtrTable, compare_step, flat_inputs, hp_dict, hp_struct, l2_terms, np_of, oracle_update, run_rank,
+                     stream)
 from parity import ulp_distance_f32
 
 pytestmark = pytest.mark.gpu
 
 SCHEDS = [orc.RING, orc.HRING, orc.HORING]
-
-
-def _flat_inputs(P, n, seed, dtype=wl.BF16, integer=False, dist="normal"):
-    dev = wl.chunk_contribs(P, n, seed, dtype=dtype, device=DEV, integer=integer, dist=dist)
-    return dev, [np_of(t) for t in dev]
-
-
-def _run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, step, report=None, check_unfused=True):
-    """One rank, chunk layout: reduce, fused step, unfused step; all against the oracle."""
-    ob, ol = orc.state_range(lay, rank, strategy[2])
-    contrib = [t[ob:ob + ol] for t in dev]
-    g = torch.empty(ol, dtype=torch.float32, device=DEV)
-    ss = torch.zeros(1, dtype=torch.float64, device=DEV)
-    paro.paro_reduce_shard(pl, rank, [c.data_ptr() for c in contrib], paro.PARO_CHUNK, g.data_ptr(), ss.data_ptr(),
-                           stream())
-    g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, [h[ob:ob + ol] for h in host], "chunk")
-    g_gpu = np_of(g)
-    what = f"{strategy}/sched{sched}/rank{rank}"
-    assert g_gpu.tobytes() == g_ref.tobytes(), what + ": reduced gradient differs"
-    assert abs(float(ss.item()) - ss_ref) <= 1e-12 * ss_ref, what
-
-    p0, m0, v0 = (a[ob:ob + ol].copy() for a in state)
-    total = ss_ref
-    ref = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=step)
-    lit = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=step, literal32=True)
-    g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
-
-    dst_len, slot_off, slot_len = orc.pack_slot(lay, rank, strategy)
-    assert slot_len == ol
-
-    def fresh():
-        return [torch.from_numpy(a.copy()).to(DEV) for a in (p0, m0, v0)]
-
-    # fused
-    p, m, v = fresh()
-    dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
-    gs = torch.empty(ol, dtype=torch.float32, device=DEV)
-    ss2 = torch.zeros(1, dtype=torch.float64, device=DEV)
-    paro.paro_step_fused(pl, rank, [c.data_ptr() for c in contrib], paro.PARO_CHUNK, hp_struct(paro, hp, step),
-                         gs.data_ptr(), ss2.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(),
-                         stream())
-    q_all = np_of(dst)
-    fused = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=q_all[slot_off:slot_off + slot_len])
-    compare_step(fused, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=what + " fused", report=report, literal=lit)
-    assert (fused["q"] == orc.bf16_rne(fused["p"])).all(), what + ": pack is not the rounding of the stored p"
-    assert not q_all[:slot_off].any() and not q_all[slot_off + slot_len:].any(), what + ": wrote outside the slot"
-    if hp["max_norm"] > 0:
-        assert np_of(gs).tobytes() == g_ref.tobytes() and abs(float(ss2.item()) - ss_ref) <= 1e-12 * ss_ref
-
-    if check_unfused:
-        p, m, v = fresh()
-        dst2 = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
-        tot = torch.tensor([total], dtype=torch.float64, device=DEV)
-        paro.paro_adam_shard(pl, rank, hp_struct(paro, hp, step), g.data_ptr(), tot.data_ptr(), p.data_ptr(),
-                             m.data_ptr(), v.data_ptr(), 0, stream())
-        paro.paro_pack_params(pl, rank, p.data_ptr(), dst2.data_ptr(), stream())
-        for name, t in (("p", p), ("m", m), ("v", v)):
-            assert np_of(t).tobytes() == fused[name].tobytes(), what + f": unfused {name} differs from fused"
-        assert np_of(dst2).tobytes() == q_all.tobytes()
-    return fused, ref
 
 
 def test_tiny_every_strategy_and_schedule(paro):
@@ -82,7 +23,7 @@ def test_tiny_every_strategy_and_schedule(paro):
     P, G = cfg.P, cfg.G
     lay = orc.layout(P, G, cfg.sizes)
     n = P * lay.L
-    dev, host = _flat_inputs(P, n, seed=0)
+    dev, host = flat_inputs(P, n, seed=0)
     state = [np_of(t) for t in wl.master_state(n, 0)]
     hp = hp_dict(P)
     report = []
@@ -91,7 +32,7 @@ def test_tiny_every_strategy_and_schedule(paro):
         for sched in SCHEDS:
             pl = paro.paro_plan(P, G, strategy, cfg.sizes, sched=sched)
             for rank in range(P):
-                fused, _ = _run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, 1, report,
+                fused, _ = run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, 1, report,
                                      check_unfused=(sched == orc.HORING))
                 ob, ol = orc.state_range(lay, rank, strategy[2])
                 key = (sched,)
@@ -116,7 +57,7 @@ def test_fp32_literal_evaluation_distance(paro):
     P, G = 4, 2
     lay = orc.layout(P, G, [1 << 18])
     n = P * lay.L
-    dev, host = _flat_inputs(P, n, seed=3)
+    dev, host = flat_inputs(P, n, seed=3)
     state = [np_of(t) for t in wl.master_state(n, 3)]
     state[1] = np_of(wl.draw(n, 91, scale=1e-4, dtype=wl.F32))
     state[2] = np.abs(np_of(wl.draw(n, 92, scale=1e-7, dtype=wl.F32)))
@@ -124,7 +65,7 @@ def test_fp32_literal_evaluation_distance(paro):
     for max_norm, adamw, step in ((0.0, True, 1), (0.05, True, 4), (0.05, False, 9)):
         hp = hp_dict(P, max_norm=max_norm, adamw=adamw)
         rank = 2
-        fused, ref = _run_rank(paro, pl, lay, "GGG", orc.HORING, rank, dev, host, state, hp, step)
+        fused, ref = run_rank(paro, pl, lay, "GGG", orc.HORING, rank, dev, host, state, hp, step)
         ob, ol = orc.state_range(lay, rank, "G")
         g_ref, ss_ref = orc.reduce_shard(lay, "GGG", orc.HORING, rank, [h[ob:ob + ol] for h in host], "chunk")
         lit = oracle_update(lay, "GGG", rank, g_ref, *(a[ob:ob + ol] for a in state), total_sumsq=ss_ref, hp=hp,
@@ -142,7 +83,7 @@ def test_integer_gradients_reduce_exactly(paro):
     lay = orc.layout(P, G, [P * 5000 + 13])
     n = P * lay.L
     for dtype in (wl.BF16, wl.F32):
-        dev, host = _flat_inputs(P, n, seed=11, dtype=dtype, integer=True)
+        dev, host = flat_inputs(P, n, seed=11, dtype=dtype, integer=True)
         as_f32 = [orc.bf16_bits_to_f32(h) if h.dtype == np.uint16 else h for h in host]
         exact = np.sum([a.astype(np.int64) for a in as_f32], axis=0)
         for sched in SCHEDS:
@@ -164,12 +105,12 @@ def test_fp32_contributions_chunk_layout(paro):
     sizes = [70001]
     lay = orc.layout(P, G, sizes)
     n = P * lay.L
-    dev, host = _flat_inputs(P, n, seed=21, dtype=wl.F32)
+    dev, host = flat_inputs(P, n, seed=21, dtype=wl.F32)
     state = [np_of(t) for t in wl.master_state(n, 21)]
     for strategy, sched in (("IIG", orc.HORING), ("NNI", orc.HRING), ("GGG", orc.RING)):
         pl = paro.paro_plan(P, G, strategy, sizes, sched=sched, grad_dtype=[wl.F32])
         for rank in range(P):
-            _run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp_dict(P, max_norm=0.01), 3)
+            run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp_dict(P, max_norm=0.01), 3)
 
 
 @pytest.mark.parametrize("P,G,total", [(1, 1, 1), (1, 1, 4099), (4, 2, 1), (4, 4, 3), (8, 2, 8 * 8 * 300 - 1),
@@ -181,7 +122,7 @@ def test_layout_edge_cases(paro, P, G, total):
     block of 256 elements, one block plus 8 with a ragged end."""
     lay = orc.layout(P, G, [total])
     n = P * lay.L
-    dev, host = _flat_inputs(P, n, seed=31)
+    dev, host = flat_inputs(P, n, seed=31)
     for t, h in zip(dev, host):                 # padding carries zero gradient
         t[total:] = 0
         h[total:] = 0
@@ -192,7 +133,7 @@ def test_layout_edge_cases(paro, P, G, total):
     pl = paro.paro_plan(P, G, "GGG", [total])
     ranks = sorted({0, P - 1, P // 2})
     for rank in ranks:
-        fused, ref = _run_rank(paro, pl, lay, "GGG", sched, rank, dev, host, state, hp_dict(P, max_norm=1e-4), 2)
+        fused, ref = run_rank(paro, pl, lay, "GGG", sched, rank, dev, host, state, hp_dict(P, max_norm=1e-4), 2)
         ob, ol = orc.state_range(lay, rank, "G")
         pad = slice(max(0, total - ob), ol)
         for k in ("p", "m", "v", "q"):
@@ -248,7 +189,7 @@ def test_runs_are_bit_identical(paro):
     P, G = 16, 8
     sizes = [16 * 3 * 2048 * 11]
     lay = orc.layout(P, G, sizes)
-    dev, _ = _flat_inputs(P, lay.L, seed=41)
+    dev, _ = flat_inputs(P, lay.L, seed=41)
     pl = paro.paro_plan(P, G, "IIG", sizes)
     outs = []
     for _ in range(3):
@@ -372,7 +313,7 @@ def test_chunk_layout_with_decay_mask(paro):
     lay = orc.layout(P, G, sizes)
     sched = orc.default_sched(P, G)
     n = P * lay.L
-    dev, host = _flat_inputs(P, n, seed=81)
+    dev, host = flat_inputs(P, n, seed=81)
     for t, h in zip(dev, host):
         t[lay.total:] = 0
         h[lay.total:] = 0
