@@ -37,7 +37,12 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_share",
-                    choices=["llama7b_share", "llama65b_share", "tiny_share"])
+                    choices=["llama7b_share", "llama65b_share", "tiny_share", "ragged", "ragged_large"],
+                    help="llama7b_share: the configuration the metric is quoted on.  ragged: the 10 000-tensor list "
+                         "(sizes log-uniform in [1, 65536], 25 %% fp32 / 75 %% bf16 gradients, P = 8, G = 4; a shard of "
+                         "7.3 M parameters, cache-resident - no roofline claim); ragged_large: the same law with 160 000 "
+                         "tensors (a shard of about 118 M parameters, 2.4 GB of contributions per sweep).  Both use the "
+                         "tensor layout")
     ap.add_argument("--no-clip", action="store_true", help="single-sweep path (max_norm = 0)")
     ap.add_argument("--layout", default="chunk", choices=["chunk", "tensors"],
                     help="chunk: contributions are buffers in shard coordinates (the default, the configuration the "
@@ -106,24 +111,40 @@ def main():
         print(json.dumps({"copy_ref_bytes_read": 4 << 30, "copy_ref_bytes_written": 4 << 30, "launches": 3}))
         return
 
+    ragged = args.workload.startswith("ragged")
     if args.workload == "tiny_share":           # quick functional check of the script itself
         cfg = wl.Config("tiny_share", 16, 8, "IIG", [16 * 2048 * 64], max_norm=1.0)
+    elif args.workload == "ragged_large":       # the ragged list's law, 16 times as many tensors
+        cfg = wl.config("ragged")
+        cfg.sizes, cfg.dtypes = wl.ragged_sizes(160000, seed=5), wl.ragged_dtypes(160000, seed=55)
     else:
         cfg = wl.config(args.workload)
+    if ragged:
+        args.layout = "tensors"
+        args.no_cpu_baseline = True             # the oracle is timed on the headline workload only
     P, G, strategy = cfg.P, cfg.G, cfg.strategy
-    rank = 5 if P == 16 else (21 if P == 64 else 0)
+    rank = 5 if P == 16 else (21 if P == 64 else (3 if ragged else 0))
     max_norm = 0.0 if args.no_clip else cfg.max_norm
     sizes = cfg.sizes
-    if args.layout == "tensors":
+    if args.layout == "tensors" and not ragged:
         assert args.workload == "llama7b_share", "--layout tensors goes with the llama7b_share workload"
         sizes = wl.llama7b_sizes()                 # the same Psi as a list of 291 tensors
-    pl = paro.paro_plan(P, G, strategy, sizes)
+    pl = paro.paro_plan(P, G, strategy, sizes, grad_dtype=cfg.dtypes)
     L = paro.paro_shard_len(pl)
     ob, ol = paro.paro_range(pl, rank, "O")
     assert ol == L
     dst_len, slot_off, slot_len = paro.paro_pack_slot(pl, rank)
 
-    if args.layout == "tensors":
+    contrib_bytes_per_rank = 2 * L              # bytes one rank contributes to the range (bf16)
+    if ragged:
+        sets = wl.tensor_contribs(P, sizes, cfg.dtypes, 7, 1, dist=cfg.dist, device=dev)
+        tables = [torch.tensor([t.data_ptr() if t.numel() else 0 for t in ts.tensors], dtype=torch.int64, device=dev)
+                  for ts in sets]
+        ptrs = [t.data_ptr() for t in tables]
+        layout = paro.PARO_TENSORS
+        contrib = None
+        contrib_bytes_per_rank = sum(n * (4 if cfg.dtypes[t] == wl.F32 else 2) for (t, _o, _s, n) in paro.paro_segments(pl, rank))
+    elif args.layout == "tensors":
         # per simulated rank, only the tensors that meet this rank's range exist; the pointer table gives
         # the others a valid address, which the step never reads
         sets = wl.tensor_contribs_over_range(P, sizes, ob, ol, 7, device=dev)
@@ -199,8 +220,8 @@ def main():
     ms_fused_entry = (time.perf_counter() - t0) * 1e3 / K
 
     clip = max_norm > 0
-    bytes_step = (2 * P + (34 if clip else 26)) * L
-    bytes_dom = (2 * P + (4 if clip else 26)) * L
+    bytes_step = P * contrib_bytes_per_rank + (34 if clip else 26) * L
+    bytes_dom = P * contrib_bytes_per_rank + (4 if clip else 26) * L
     dom_ms = ms1
     achieved = bytes_dom / (dom_ms * 1e-3) / 1e9
     dom_kernel = ("k_reduce4t" if args.layout == "tensors" else "k_reduce4") if clip else "k_fused4"
@@ -220,16 +241,17 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "layout": args.layout, "P": P, "G": G, "strategy": strategy,
                    "schedule": ["ring", "h-ring", "ho-ring"][paro.paro_sched(pl)], "rank": rank,
-                   "shard_params": L, "contrib_dtype": "bf16", "clip_max_norm": max_norm,
+                   "shard_params": L, "contrib_dtype": "bf16/f32 per tensor" if ragged else "bf16", "tensors": len(sizes),
+                   "clip_max_norm": max_norm,
                    "sweeps": 2 if clip else 1},
         "hbm_gbps_step": bytes_step / (ms_step * 1e-3) / 1e9,
         "hbm_frac_step": bytes_step / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-        "algorithmic_bytes_per_param_step": 2 * P + (34 if clip else 26),
+        "algorithmic_bytes_per_param_step": bytes_step / L,
         "ms_fused_entry": ms_fused_entry,
         "ms_per_step_device": stats(step_ev),
         "library": library_identity(),
         "kernels": {
-            "sweep1_fold_sumsq": {"ms": ms1, "ms_stats": stats(sweep1), "bytes_per_param": 2 * P + (4 if clip else 26),
+            "sweep1_fold_sumsq": {"ms": ms1, "ms_stats": stats(sweep1), "bytes_per_param": bytes_dom / L,
                                   "gbps": bytes_dom / (ms1 * 1e-3) / 1e9,
                                   "gbps_median": bytes_dom / (float(np.median(sweep1)) * 1e-3) / 1e9,
                                   "gbps_best": bytes_dom / (min(sweep1) * 1e-3) / 1e9},
@@ -271,7 +293,21 @@ def main():
     out["roofline"]["frac_of_copy"] = achieved / copy_gbps
     out["hbm_frac_of_copy_step"] = out["hbm_gbps_step"] / copy_gbps
 
-    if args.extras:
+    if ragged:
+        # the chunk layout at the same shard size and rank count (all-bf16 contributions in shard coordinates):
+        # what the tensor layout's bookkeeping costs on top of the plain sweeps
+        cpl = paro.paro_plan(P, G, strategy, [P * L])
+        cc = wl.chunk_contribs(P, L, 9, device=dev)
+        cptrs = [t.data_ptr() for t in cc]
+        ms_c1 = timed(lambda: paro.paro_reduce_shard(cpl, rank, cptrs, paro.PARO_CHUNK, g.data_ptr(), ss.data_ptr(), st), 20)
+        out["chunk_layout_ref"] = {"sweep1_ms": ms_c1, "bytes_per_param": 2 * P + 4,
+                                   "gbps": (2 * P + 4) * L / (ms_c1 * 1e-3) / 1e9,
+                                   "tensor_layout_sweep1_over_chunk_layout": float(np.median(sweep1)) / ms_c1,
+                                   "tensor_layout_sweep1_gbps_over_chunk_layout":
+                                       bytes_dom / (float(np.median(sweep1)) * 1e-3) / 1e9 / ((2 * P + 4) * L / (ms_c1 * 1e-3) / 1e9)}
+        del cc
+
+    if args.extras and not ragged:
         wire = torch.zeros(L, dtype=torch.float32, device=dev)          # partial arriving over the ring (fp32)
         ms_hop = timed(lambda: paro.paro_ring_hop(pl, wire.data_ptr(), paro.PARO_F32, contrib[0].data_ptr(),
                                                   paro.PARO_BF16, g.data_ptr(), L, st))
