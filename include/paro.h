@@ -51,7 +51,7 @@
  * offset tables and a scratch array of partial sums (8 bytes per 256 elements
  * of a chunk); the first call for a rank that uses the tensor layout or a
  * weight-decay mask adds a per-tile table for each chunk of that rank's update
- * range (16 bytes per 2048 elements, built when the chunk has at most 4 Mi
+ * range (16 bytes per 256 elements, built when the chunk has at most 4 Mi
  * tiles, or at most PARO_TILE_TABLE_MAX_TILES when that environment variable
  * is set; without it the kernels search).  Those first calls allocate and copy
  * synchronously - make them outside any stream capture; every later call only

@@ -29,7 +29,7 @@ namespace {
 #define PARO_BATCH 16               // contributions loaded before the first is consumed
 #endif
 #ifndef PARO_LANE_BATCH
-#define PARO_LANE_BATCH 4          // ... in a block with a tensor boundary inside (element loads)
+#define PARO_LANE_BATCH 4          // ... in a block with a tensor boundary inside (element loads; more costs registers for nothing)
 #endif
 // One-wave blocks in flight per compute unit (0 = as many as fit).  The mixed read/write sweeps
 // run faster with fewer requests outstanding than the registers would allow.  For the fold the
@@ -48,6 +48,19 @@ namespace {
 #ifndef PARO_ADAM_MASK_WAVES_PER_CU
 #define PARO_ADAM_MASK_WAVES_PER_CU 16   // with a decay mask: a table look-up per wave to hide as well
 #endif
+// Sweep 1 in the tensor layout lets a wave take two consecutive blocks when there are at most this
+// many contributions and the launch has at least that many blocks (see k_reduce4t; a small launch
+// wants as many waves as it can get).  Its budget of loads in flight is larger than the chunk
+// layout's: its waves spend part of their life on look-ups, with no data in flight.
+#ifndef PARO_PAIR_MAX_RANKS
+#define PARO_PAIR_MAX_RANKS 8
+#endif
+#ifndef PARO_PAIR_MIN_BLOCKS
+#define PARO_PAIR_MIN_BLOCKS 131072
+#endif
+#ifndef PARO_FOLD_T_LOADS_PER_CU
+#define PARO_FOLD_T_LOADS_PER_CU 448
+#endif
 #ifndef PARO_HOP_WAVES_PER_CU
 #define PARO_HOP_WAVES_PER_CU 0
 #endif
@@ -55,13 +68,13 @@ namespace {
 #define PARO_COPY_WAVES_PER_CU 0
 #endif
 
-constexpr int WAVE = 64;              // threads of a block: every sweep kernel runs in one-wave blocks
+constexpr int WAVE = 64;              // a wave handles one piece of a sweep; most kernels run in one-wave blocks
 constexpr int EPT = 4;                // elements per thread
 constexpr int PIECE = WAVE * EPT;     // elements per block
 constexpr int TILE = PARO_TILE;       // granularity of the plan's per-tile table
 constexpr int FINALIZE_TPB = 256;     // threads of the kernel that adds the partial sums
 constexpr int FINALIZE_CHUNK = 2048;  // partials per block in its first level
-static_assert(TILE % PIECE == 0, "a block must lie inside one tile");
+static_assert(TILE == PIECE, "the per-tile table has one entry per block");
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -82,13 +95,17 @@ struct AdamConsts {
 struct TensorMap {
     const int64_t *nz_off;      // [n_nz + 1] flat start of every non-empty tensor, then Psi
     const int32_t *nz_tensor;   // [n_nz]
+    const uint8_t *nz_dtype;    // [n_nz] gradient dtype of that tensor
     const uint8_t *dtype;       // [T]
     const uint8_t *no_decay;    // [T]
     int n_nz;
     int64_t total;              // Psi
     int64_t begin;              // flat index of the launch's element 0
-    const paro_tile_info *tile_tab;   // the per-tile table from the launch's element 0 on, or null
+    const paro_tile_info *tile_tab;   // the per-tile table of the launch's chunk, or null
 };
+
+// Lane of the thread in its wave (the sweep kernels run in one-wave blocks).
+__device__ __forceinline__ unsigned lane_id() { return threadIdx.x & (WAVE - 1); }
 
 // ---------------------------------------------------------------- small helpers
 __device__ __forceinline__ float bf16_lo(unsigned int w) { return __uint_as_float(w << 16); }

@@ -108,27 +108,25 @@ __device__ __forceinline__ void update4(const AdamConsts &a, float sc, const boo
 #pragma unroll
     for (int i = 0; i < 4; ++i) adam1(a, sc, decays[i], gg[i], pp[i], mm[i], vv[i]);
     constexpr int ST = PARO_POL_STATE_ST;
-    buf_store16<ST>(as_u32x4(pp[0], pp[1], pp[2], pp[3]), wave_buffer(p + e0, elems * 4), threadIdx.x * 16);
-    buf_store16<ST>(as_u32x4(mm[0], mm[1], mm[2], mm[3]), wave_buffer(m + e0, elems * 4), threadIdx.x * 16);
-    buf_store16<ST>(as_u32x4(vv[0], vv[1], vv[2], vv[3]), wave_buffer(v + e0, elems * 4), threadIdx.x * 16);
+    buf_store16<ST>(as_u32x4(pp[0], pp[1], pp[2], pp[3]), wave_buffer(p + e0, elems * 4), lane_id() * 16);
+    buf_store16<ST>(as_u32x4(mm[0], mm[1], mm[2], mm[3]), wave_buffer(m + e0, elems * 4), lane_id() * 16);
+    buf_store16<ST>(as_u32x4(vv[0], vv[1], vv[2], vv[3]), wave_buffer(v + e0, elems * 4), lane_id() * 16);
     if (PACK) {
         const u32x2 w = {pack2_lowp(pp[0], pp[1], a.pack_dtype), pack2_lowp(pp[2], pp[3], a.pack_dtype)};
-        buf_store8<ST>(w, wave_buffer(dst + e0, elems * 2), threadIdx.x * 8);
+        buf_store8<ST>(w, wave_buffer(dst + e0, elems * 2), lane_id() * 8);
     }
 }
 
-// Which of the thread's 4 elements take weight decay (padding does, and stays 0).
-__device__ __forceinline__ void decay_flags(const TensorMap &tm, const Piece &pc, int64_t e, bool decays[4]) {
+// Which of the thread's 4 elements take weight decay (padding does, and stays 0).  loc: from
+// locate4 when the block holds a boundary.
+__device__ __forceinline__ void decay_flags(const TensorMap &tm, const Piece &pc, const Located &loc, bool decays[4]) {
     if (pc.tensor != -1) {
         const bool d = pc.tensor < 0 || tm.no_decay[pc.tensor] == 0;
 #pragma unroll
         for (int i = 0; i < 4; ++i) decays[i] = d;
     } else {
-        int tens[4];
-        int64_t toff[4];
-        locate4(tm, pc.seg, tm.begin + e, tens, toff);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) decays[i] = tens[i] < 0 || tm.no_decay[tens[i]] == 0;
+        for (int i = 0; i < 4; ++i) decays[i] = loc.tens[i] < 0 || tm.no_decay[loc.tens[i]] == 0;
     }
 }
 
@@ -152,14 +150,14 @@ __device__ __forceinline__ double sumsq4(const float X[4]) {
 // --------------------------------------------------------------------- kernels
 
 __device__ __forceinline__ void store_g4(float *g, int64_t e0, unsigned elems, const float X[4]) {
-    buf_store16<PARO_POL_G_ST>(as_u32x4(X[0], X[1], X[2], X[3]), wave_buffer(g + e0, elems * 4), threadIdx.x * 16);
+    buf_store16<PARO_POL_G_ST>(as_u32x4(X[0], X[1], X[2], X[3]), wave_buffer(g + e0, elems * 4), lane_id() * 16);
 }
 
 // Sweep 1, chunk layout: g = fold of the contributions; optional per-block partial of sum g^2.
 template <int DT, bool SUMSQ>
 __global__ __launch_bounds__(WAVE) void k_reduce4(const SrcTable src, int P, int group_len, int64_t n,
                                                   float *__restrict__ g, double *__restrict__ partials) {
-    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    const int64_t e0 = block_first(), e = e0 + lane_id() * EPT;
     double acc = 0.0;
     if (e < n) {
         const unsigned elems = piece_elems(e0, n);
@@ -171,30 +169,66 @@ __global__ __launch_bounds__(WAVE) void k_reduce4(const SrcTable src, int P, int
     }
     if (SUMSQ) {
         const double s = wave_sum(acc);
-        if (threadIdx.x == 0) partials[partial_slot()] = s;
+        if (lane_id() == 0) partials[partial_slot()] = s;
     }
 }
 
-// Sweep 1, tensor layout.
-template <bool SUMSQ>
+// Sweep 1, tensor layout: one block of 256 elements starting at e0 < n.  Every lane of the wave takes part.
+template <bool SUMSQ, int KB>
+__device__ __forceinline__ void reduce_piece_t(const TensorMap &tm, const Piece &pc, const SrcTable &src, int P,
+                                               int group_len, int64_t n, int64_t e0, float *g, double &acc) {
+    const int64_t e = e0 + lane_id() * EPT;
+    Located loc;
+    if (pc.tensor == -1) locate4(tm, pc.seg, tm.begin + e0, lane_id() * EPT, loc);     // the whole wave
+    if (e < n) {
+        const unsigned elems = piece_elems(e0, n);
+        float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};           // padding: the sum of zeros
+        if (pc.tensor != -2) fold_tensors<KB>(pc, loc, src, P, group_len, X);
+        store_g4(g, e0, elems, X);
+        if (SUMSQ) acc += sumsq4(X);
+    }
+}
+
+// A wave takes PPW consecutive blocks.  PPW = 2 is for few contributions (P <= 8): where both
+// blocks lie inside one tensor - the usual case - the wave folds them as one stream of 512
+// elements per contribution: one look-up and twice the bytes in flight per wave; the cache line
+// that the two blocks share (a block does not start on a line inside its tensor) is fetched once.
+// KB: contributions loaded before the first is consumed (8 when launched for P <= 8 only: fewer
+// registers, more waves).
+template <bool SUMSQ, int PPW, int KB>
 __global__ __launch_bounds__(WAVE) void k_reduce4t(const SrcTable src, int P, int group_len, int64_t n,
                                                    float *__restrict__ g, double *__restrict__ partials,
                                                    const TensorMap tm) {
-    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    const int64_t e0 = (int64_t)blockIdx.x * (PPW * PIECE);
     double acc = 0.0;
     if (e0 < n) {                                            // wave-uniform
-        const Piece pc = piece_of(tm, e0, n);
-        if (e < n) {
-            const unsigned elems = piece_elems(e0, n);
-            float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};           // padding: the sum of zeros
-            if (pc.tensor != -2) fold_tensors(tm, pc, e, src, P, group_len, X);
-            store_g4(g, e0, elems, X);
-            if (SUMSQ) acc = sumsq4(X);
+        bool done = false;
+        if constexpr (PPW == 2) {
+            if (e0 + 2 * PIECE <= n) {                       // two whole blocks
+                const Piece pa = piece_of(tm, e0, n), pb = piece_of(tm, e0 + PIECE, n);
+                if (pa.tensor >= 0 && pb.tensor == pa.tensor) {                         // ... inside one tensor
+                    float X[8];
+                    fold_tensor_pair(pa, src, P, group_len, X);
+                    const wave_buf out = wave_buffer(g + e0, 2 * PIECE * 4);
+                    buf_store16<PARO_POL_G_ST>(as_u32x4(X[0], X[1], X[2], X[3]), out, lane_id() * 16);
+                    buf_store16<PARO_POL_G_ST>(as_u32x4(X[4], X[5], X[6], X[7]), out, PIECE * 4 + lane_id() * 16);
+                    if (SUMSQ) acc = sumsq4(X) + sumsq4(X + 4);
+                    done = true;
+                }
+            }
+        }
+        if (!done) {                                         // block by block (one copy of the code: no unrolling)
+#pragma unroll 1
+            for (int j = 0; j < PPW; ++j) {
+                const int64_t ej = e0 + (int64_t)j * PIECE;
+                if (ej < n)
+                    reduce_piece_t<SUMSQ, KB>(tm, piece_of(tm, ej, n), src, P, group_len, n, ej, g, acc);
+            }
         }
     }
     if (SUMSQ) {
         const double s = wave_sum(acc);
-        if (threadIdx.x == 0) partials[partial_slot()] = s;
+        if (lane_id() == 0) partials[partial_slot()] = s;
     }
 }
 
@@ -226,16 +260,20 @@ __global__ __launch_bounds__(WAVE) void k_adam4(const AdamConsts a, const double
     // an overflowed (non-finite) gradient makes its sum of squares non-finite: the whole step is skipped
     if (a.skip_nonfinite && !isfinite(*total_sumsq)) return;
     const float sc = scale_from_norm(a, total_sumsq);
-    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    const int64_t e0 = block_first(), e = e0 + lane_id() * EPT;
     if (e0 >= n) return;
     bool decays[4] = {true, true, true, true};
     Piece pc;
-    if (MASK) pc = piece_of(tm, e0, n);
+    Located loc;
+    if (MASK) {
+        pc = piece_of(tm, e0, n);
+        if (pc.tensor == -1) locate4(tm, pc.seg, tm.begin + e0, lane_id() * EPT, loc);     // the whole wave
+    }
     if (e >= n) return;
     const unsigned elems = piece_elems(e0, n);
     const u32x4 G = ld_nt(reinterpret_cast<const u32x4 *>(g + e));
     const State4 s = load_state4(p, m, v, e);
-    if (MASK) decay_flags(tm, pc, e, decays);
+    if (MASK) decay_flags(tm, pc, loc, decays);
     const float gg[4] = {__uint_as_float(G.x), __uint_as_float(G.y), __uint_as_float(G.z), __uint_as_float(G.w)};
     update4<PACK>(a, sc, decays, gg, s, p, m, v, dst, e0, elems);
 }
@@ -248,35 +286,39 @@ __global__ __launch_bounds__(WAVE) void k_fused4(const SrcTable src, int P, int 
                                                  const AdamConsts a, float *__restrict__ p, float *__restrict__ m,
                                                  float *__restrict__ v, uint16_t *__restrict__ dst,
                                                  const TensorMap tm) {
-    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    const int64_t e0 = block_first(), e = e0 + lane_id() * EPT;
     if (e0 >= n) return;
     Piece pc;
-    if (TENSORS || MASK) pc = piece_of(tm, e0, n);
+    Located loc;
+    if (TENSORS || MASK) {
+        pc = piece_of(tm, e0, n);
+        if (pc.tensor == -1) locate4(tm, pc.seg, tm.begin + e0, lane_id() * EPT, loc);     // the whole wave
+    }
     if (e >= n) return;
     const unsigned elems = piece_elems(e0, n);
     const State4 s = load_state4(p, m, v, e);
     float X[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     if constexpr (TENSORS) {
-        if (pc.tensor != -2) fold_tensors(tm, pc, e, src, P, group_len, X);
+        if (pc.tensor != -2) fold_tensors(pc, loc, src, P, group_len, X);
     } else {
         Chunk4Loader<DT> ld{e};
         fold4(ld, src, P, group_len, X);
     }
     bool decays[4] = {true, true, true, true};
-    if (MASK) decay_flags(tm, pc, e, decays);
+    if (MASK) decay_flags(tm, pc, loc, decays);
     update4<true>(a, a.grad_scale, decays, X, s, p, m, v, dst, e0, elems);
 }
 
 // Low-precision pack alone.
 __global__ __launch_bounds__(WAVE) void k_pack(const float *__restrict__ p, uint16_t *__restrict__ dst, int64_t n,
                                                int pack_dtype) {
-    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    const int64_t e0 = block_first(), e = e0 + lane_id() * EPT;
     if (e >= n) return;
     const unsigned elems = piece_elems(e0, n);
     const u32x4 P = ld_nt(reinterpret_cast<const u32x4 *>(p + e));
     const u32x2 w = {pack2_lowp(__uint_as_float(P.x), __uint_as_float(P.y), pack_dtype),
                      pack2_lowp(__uint_as_float(P.z), __uint_as_float(P.w), pack_dtype)};
-    buf_store8<PARO_POL_LIGHT_ST>(w, wave_buffer(dst + e0, elems * 2), threadIdx.x * 8);
+    buf_store8<PARO_POL_LIGHT_ST>(w, wave_buffer(dst + e0, elems * 2), lane_id() * 8);
 }
 
 // One ring hop / one accumulation: out = a + b, element by element in fp32.  n may be any
@@ -295,14 +337,14 @@ __device__ __forceinline__ float hop_load1(const void *a, int64_t i) {
 
 template <int DA, int DB>
 __global__ __launch_bounds__(WAVE) void k_hop(const void *a, const void *b, float *out, int64_t n) {
-    const int64_t e0 = block_first(), e = e0 + threadIdx.x * EPT;
+    const int64_t e0 = block_first(), e = e0 + lane_id() * EPT;
     const unsigned whole = piece_elems(e0, n) & ~3u;       // elements of the block in whole groups of 4
     if (e + EPT <= n) {
         float x[4], y[4];
         hop_load4<DA>(a, e, x);
         hop_load4<DB>(b, e, y);
         buf_store16<PARO_POL_LIGHT_ST>(as_u32x4(x[0] + y[0], x[1] + y[1], x[2] + y[2], x[3] + y[3]),
-                                       wave_buffer(out + e0, whole * 4), threadIdx.x * 16);
+                                       wave_buffer(out + e0, whole * 4), lane_id() * 16);
     } else {
         for (int64_t i = e; i < n; ++i) out[i] = hop_load1<DA>(a, i) + hop_load1<DB>(b, i);
     }
@@ -314,7 +356,7 @@ __global__ __launch_bounds__(WAVE) void k_copy16(const u32x4 *__restrict__ src, 
     if (i0 + threadIdx.x >= n) return;
     const unsigned bytes = (unsigned)min((int64_t)WAVE, n - i0) * 16;
     const u32x4 v = ld_nt(src + i0 + threadIdx.x);
-    buf_store16<PARO_POL_LIGHT_ST>(v, wave_buffer(dst + i0, bytes), threadIdx.x * 16);
+    buf_store16<PARO_POL_LIGHT_ST>(v, wave_buffer(dst + i0, bytes), lane_id() * 16);
 }
 
 }  // namespace
@@ -338,9 +380,9 @@ int check_ptr(const void *p, const char *what) {
     return PARO_OK;
 }
 
-// One-wave blocks of a sweep over n elements.
-unsigned piece_grid(int64_t n) {
-    const int64_t nb = (n + PIECE - 1) / PIECE;
+// One-wave blocks of a sweep over n elements, ppw pieces per wave.
+unsigned piece_grid(int64_t n, int ppw = 1) {
+    const int64_t nb = (n + (int64_t)PIECE * ppw - 1) / ((int64_t)PIECE * ppw);
     return (unsigned)(nb < 1 ? 1 : nb);
 }
 
@@ -388,6 +430,7 @@ void free_tables(paro_device_tables &d) {
     // best effort: at process exit the runtime may already be gone
     (void)hipFree(d.nz_off);
     (void)hipFree(d.nz_tensor);
+    (void)hipFree(d.nz_dtype);
     (void)hipFree(d.dtype);
     (void)hipFree(d.no_decay);
     for (paro_tile_info *t : d.tile_tab) (void)hipFree(t);
@@ -399,6 +442,9 @@ int fill_tables(const paro_plan_t *pl, paro_device_tables &d) {
     int rc;
     if ((rc = upload(&d.nz_off, pl->nz_off.data(), pl->nz_off.size()))) return rc;
     if ((rc = upload(&d.nz_tensor, pl->nz_tensor.data(), pl->nz_tensor.size()))) return rc;
+    std::vector<uint8_t> nz_dtype(pl->nz_tensor.size());
+    for (size_t k = 0; k < nz_dtype.size(); ++k) nz_dtype[k] = pl->dtype[(size_t)pl->nz_tensor[k]];
+    if ((rc = upload(&d.nz_dtype, nz_dtype.data(), nz_dtype.size()))) return rc;
     if ((rc = upload(&d.dtype, pl->dtype.data(), pl->dtype.size()))) return rc;
     if ((rc = upload(&d.no_decay, pl->no_decay.data(), pl->no_decay.size()))) return rc;
     d.tiles_per_chunk = (pl->L + TILE - 1) / TILE;
@@ -503,7 +549,7 @@ TensorMap map_for(const paro_plan_t *pl, const Scratch &sc, int64_t begin, bool 
     if (!sc.plan_tables) {                  // launches that never look at tensors (chunk layout, no decay mask)
         tm.nz_off = nullptr;
         tm.nz_tensor = nullptr;
-        tm.dtype = tm.no_decay = nullptr;
+        tm.nz_dtype = tm.dtype = tm.no_decay = nullptr;
         tm.n_nz = 0;
         tm.total = pl->total;
         tm.begin = begin;
@@ -512,6 +558,7 @@ TensorMap map_for(const paro_plan_t *pl, const Scratch &sc, int64_t begin, bool 
     }
     tm.nz_off = pl->dev.nz_off;
     tm.nz_tensor = pl->dev.nz_tensor;
+    tm.nz_dtype = pl->dev.nz_dtype;
     tm.dtype = pl->dev.dtype;
     tm.no_decay = pl->dev.no_decay;
     tm.n_nz = (int)pl->nz_tensor.size();
@@ -605,15 +652,29 @@ int launch_reduce(const paro_plan_t *pl, const Scratch &sc, int layout, const Sr
                   float *g, hipStream_t st) {
     const int64_t n = pl->L;
     double *partials = sc.partials;
-    const unsigned grid = (piece_grid(n) + 7u) & ~7u;       // a multiple of 8: see partial_slot()
     if (layout == PARO_CHUNK) {
+        const unsigned grid = (piece_grid(n) + 7u) & ~7u;       // a multiple of 8: see partial_slot()
         const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
         PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_reduce4<DT, SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P,
                                                        group_len, n, g, partials));
+        return (int)grid;
+    }
+    const TensorMap tm = map_for(pl, sc, c * pl->L, true);
+    if (pl->P <= PARO_PAIR_MAX_RANKS && piece_grid(n) >= PARO_PAIR_MIN_BLOCKS) {
+        // few contributions, a launch that fills the GPU many times over: two blocks per wave
+        const unsigned grid = (piece_grid(n, 2) + 7u) & ~7u;
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(2 * pl->P, 0, PARO_FOLD_T_LOADS_PER_CU));
+        hipLaunchKernelGGL((k_reduce4t<SUMSQ, 2, 8>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials, tm);
+        return (int)grid;
+    }
+    const unsigned grid = (piece_grid(n) + 7u) & ~7u;
+    if (pl->P <= PARO_PAIR_MAX_RANKS) {
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 0, PARO_FOLD_T_LOADS_PER_CU));
+        hipLaunchKernelGGL((k_reduce4t<SUMSQ, 1, 8>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials, tm);
     } else {
         const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
-        hipLaunchKernelGGL((k_reduce4t<SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials,
-                           map_for(pl, sc, c * pl->L, true));
+        hipLaunchKernelGGL((k_reduce4t<SUMSQ, 1, PARO_BATCH>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g,
+                           partials, tm);
     }
     return (int)grid;
 }
@@ -623,9 +684,9 @@ template <bool MASK>
 void launch_fused(const paro_plan_t *pl, const Scratch &sc, int layout, const SrcTable &tab, int group_len, int64_t c,
                   const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
-    const unsigned grid = piece_grid(n);
-    const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 3, PARO_FUSED_LOADS_PER_CU));
+    const int waves = fold_waves(pl->P, 3, PARO_FUSED_LOADS_PER_CU);
     const TensorMap tm = map_for(pl, sc, c * pl->L, true);
+    const unsigned grid = piece_grid(n), lds = throttle_lds(sc.lds_per_cu, waves);
     if (layout == PARO_TENSORS)
         hipLaunchKernelGGL((k_fused4<true, PARO_BF16, MASK>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, a, p, m,
                            v, dst, tm);
@@ -674,9 +735,8 @@ int launch_adam(const paro_plan_t *pl, const Scratch &sc, int rank, const AdamCo
                 const double *total_sumsq, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
-    const unsigned lds =
-        throttle_lds(sc.lds_per_cu, pl->any_no_decay ? PARO_ADAM_MASK_WAVES_PER_CU : PARO_ADAM_WAVES_PER_CU);
     if (!pl->any_no_decay) {
+        const unsigned lds = throttle_lds(sc.lds_per_cu, PARO_ADAM_WAVES_PER_CU);
         hipLaunchKernelGGL((k_adam4<PACK, false>), dim3(piece_grid(on)), dim3(WAVE), lds, st, a, total_sumsq, grad, p, m, v,
                            dst, on, map_for(pl, sc, ob, false));
         PARO_HIP(hipGetLastError());
@@ -684,6 +744,7 @@ int launch_adam(const paro_plan_t *pl, const Scratch &sc, int rank, const AdamCo
     }
     for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {      // chunk by chunk: each has its own per-tile table
         const int64_t lo = c * pl->L - ob;
+        const unsigned lds = throttle_lds(sc.lds_per_cu, PARO_ADAM_MASK_WAVES_PER_CU);
         hipLaunchKernelGGL((k_adam4<PACK, true>), dim3(piece_grid(pl->L)), dim3(WAVE), lds, st, a, total_sumsq, grad + lo,
                            p + lo, m + lo, v + lo, dst ? dst + lo : nullptr, pl->L, map_for(pl, sc, c * pl->L, true));
         PARO_HIP(hipGetLastError());

@@ -9,12 +9,12 @@
 #include "paro.h"
 
 #ifndef PARO_TILE_ELEMS
-#define PARO_TILE_ELEMS 2048
+#define PARO_TILE_ELEMS 256
 #endif
 constexpr int PARO_TILE = PARO_TILE_ELEMS;      // elements per tile of the per-tile table (a multiple of 256)
 
-// What a tile (2048 consecutive elements) of a chunk looks like, precomputed so that the kernels do
-// not have to search: tensor >= 0: the whole tile lies inside that tensor, its first element at
+// What a tile (PARO_TILE consecutive elements: by default one block's 256) of a chunk looks like,
+// precomputed so that the kernels do not have to search: tensor >= 0: the whole tile lies inside that tensor, its first element at
 // offset toff, first_seg = the tensor's gradient dtype; tensor == -1: the tile holds a tensor
 // boundary (or ends in padding), first_seg = index of its first non-empty tensor; tensor == -2:
 // the tile is all padding.
@@ -29,6 +29,7 @@ struct paro_device_tables {
     int lds_per_cu = 0;             // bytes of LDS a compute unit has (for the occupancy throttle)
     int64_t *nz_off = nullptr;      // [n_nz + 1] flat start of every non-empty tensor, then Psi
     int32_t *nz_tensor = nullptr;   // [n_nz]     index of that tensor in the caller's list
+    uint8_t *nz_dtype = nullptr;    // [n_nz]     its gradient dtype
     uint8_t *dtype = nullptr;       // [T]
     uint8_t *no_decay = nullptr;    // [T]
     // per chunk, built at the first call that works on the chunk tensor by tensor (tensor layout,
