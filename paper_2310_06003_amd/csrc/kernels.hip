@@ -660,7 +660,9 @@ int launch_reduce(const paro_plan_t *pl, const Scratch &sc, int layout, const Sr
         return (int)grid;
     }
     const TensorMap tm = map_for(pl, sc, c * pl->L, true);
-    if (pl->P <= PARO_PAIR_MAX_RANKS && piece_grid(n) >= PARO_PAIR_MIN_BLOCKS) {
+    int64_t pair_min_blocks = PARO_PAIR_MIN_BLOCKS;
+    if (const char *env = std::getenv("PARO_PAIR_MIN_BLOCKS")) pair_min_blocks = std::atoll(env);     // for tests
+    if (pl->P <= PARO_PAIR_MAX_RANKS && (int64_t)piece_grid(n) >= pair_min_blocks) {
         // few contributions, a launch that fills the GPU many times over: two blocks per wave
         const unsigned grid = (piece_grid(n, 2) + 7u) & ~7u;
         const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(2 * pl->P, 0, PARO_FOLD_T_LOADS_PER_CU));

@@ -166,6 +166,43 @@ def _tensor_layout_at_full_size(paro, sizes, P, G, strategy, rank, L_want, need_
         compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"tensor layout, block at {lo}", literal=lit)
 
 
+def test_ragged_list_at_size_two_blocks_per_wave(paro):
+    """24 000 tensors of the ragged list's law (sizes log-uniform in [1, 65536], a quarter fp32), P = 4:
+    a shard of 35 M parameters = 138 000 blocks, where sweep 1 of the tensor layout lets a wave take two
+    blocks.  One rank in full: reduced gradient and sum of squares, then the fused step."""
+    sizes, dtypes = wl.ragged_sizes(24000, seed=9), wl.ragged_dtypes(24000, seed=99)
+    P, G, strategy, rank = 4, 2, "IIG", 2
+    lay = orc.layout(P, G, sizes)
+    assert lay.L // 256 >= 131072, "the list must be large enough for the two-block shape"
+    sched = orc.default_sched(P, G)
+    pl = paro.paro_plan(P, G, strategy, sizes, grad_dtype=dtypes)
+    sets = wl.tensor_contribs(P, sizes, dtypes, 17, 1, dist="student_t", device=DEV, align_elems=1)
+    tables = [PtrTable(s.tensors) for s in sets]
+    host = []
+    for s in sets:
+        flat = {k: np_of(v) for k, v in s.flat.items()}
+        host.append([flat[dtypes[t]][s.start[t]:s.start[t] + n] for t, n in enumerate(sizes)])
+    ob, ol = orc.state_range(lay, rank, strategy[2])
+    g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, host, "tensors")
+    p, m, v = wl.master_state(ol, 18, device=DEV)
+    old = [np_of(t) for t in (p, m, v)]
+    dst_len, slot_off, slot_len = orc.pack_slot(lay, rank, strategy)
+    dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+    g = torch.empty(ol, dtype=torch.float32, device=DEV)
+    ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+    hp = hp_dict(P, max_norm=1.0)
+    paro.paro_step_fused(pl, rank, [t.ptr() for t in tables], paro.PARO_TENSORS, hp_struct(paro, hp, 1), g.data_ptr(),
+                         ss.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(), stream())
+    assert np_of(g).tobytes() == g_ref.tobytes(), "reduced gradient differs"
+    assert abs(float(ss.item()) - ss_ref) <= 1e-12 * ss_ref
+    ref = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=1)
+    lit = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=1, literal32=True)
+    assert ref["coef"] < 1.0
+    got = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=np_of(dst)[slot_off:slot_off + slot_len])
+    g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
+    compare_step(got, ref, p_old=old[0], m_old=old[1], g_hat=g_hat, what="ragged list at size", literal=lit)
+
+
 def test_llama7b_share_tensor_layout(paro):
     """The 291-tensor Llama-7B list, P = 16, rank 5's shard (20 tensors meet it)."""
     sizes = wl.llama7b_sizes()

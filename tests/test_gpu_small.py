@@ -201,13 +201,16 @@ def test_runs_are_bit_identical(paro):
     assert outs[0] == outs[1] == outs[2]
 
 
-@pytest.mark.parametrize("table", ["per-tile table", "search"])
+@pytest.mark.parametrize("table", ["per-tile table", "search", "two blocks per wave"])
 def test_tensor_layout_small_ragged(paro, table, monkeypatch):
     """Tensor layout on a small ragged list: empty and one-element tensors, mixed
     dtypes, unaligned tensor bases, a weight-decay mask, every rank, 2 steps - with
-    the plan's per-tile table and without it (every block searches the offset table)."""
+    the plan's per-tile table, without it (every block searches the offset table), and with
+    sweep 1's shape for large launches of few ranks forced on (a wave takes two blocks)."""
     if table == "search":
         monkeypatch.setenv("PARO_TILE_TABLE_MAX_TILES", "0")
+    if table == "two blocks per wave":
+        monkeypatch.setenv("PARO_PAIR_MIN_BLOCKS", "0")
     rng = np.random.default_rng(8)
     sizes = [int(s) for s in rng.integers(0, 9, 40)] + [5000, 1, 0, 7, 20000, 3, 2049, 2047, 1, 1, 9000]
     dtypes = [int(x) for x in rng.integers(0, 2, len(sizes))]
