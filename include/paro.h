@@ -228,14 +228,20 @@ int paro_adam_shard(paro_plan_t *plan, int rank, const paro_adam_t *hp, const fl
  * 16-byte aligned. */
 int paro_pack_params(paro_plan_t *plan, int rank, const float *p, uint16_t *dst_base, void *stream);
 
-/* reduce + clip + Adam + pack.  With hp->max_norm > 0 it is exactly
- * paro_reduce_shard followed by paro_adam_shard with dst_base: sweep 1 writes the
- * reduced gradient to grad_scratch (DEVICE fp32 over the update range) and the
- * sum of squares to *sumsq_scratch (DEVICE double); sweep 2 clips with THIS
- * rank's sum of squares as the total (a single-rank norm: the cross-rank sum a
- * deployment inserts between the sweeps has no peer here), updates and packs.
- * With hp->max_norm <= 0 one sweep does everything, the gradient is never
- * stored, and both scratch pointers may be NULL. */
+/* reduce + clip + Adam + pack.  With hp->max_norm > 0 or hp->skip_nonfinite it
+ * is paro_reduce_shard followed by paro_adam_shard with dst_base: sweep 1 writes
+ * the reduced gradient to grad_scratch (DEVICE fp32 over the update range) and a
+ * sum of squares to *sumsq_scratch (DEVICE double); sweep 2 takes that sum as the
+ * total, clips, updates and packs.  The sum is the norm this rank can form on its
+ * own (the cross-rank sum a deployment inserts between the sweeps has no peer
+ * here): over the rank's whole UPDATE RANGE - its own chunk when the optimizer
+ * state is sharded over all ranks ('G': the same value paro_reduce_shard gives);
+ * every chunk of its block or of the model when it is sharded inside the group
+ * only or not at all ('I', 'N': one sum per chunk, added in chunk order), so that
+ * every replica of a range clips, or skips an overflowed step, alike - and with
+ * 'N' it is the model's true norm.  With neither clipping nor skipping one sweep
+ * does everything, the gradient is never stored, and both scratch pointers may
+ * be NULL. */
 int paro_step_fused(paro_plan_t *plan, int rank, const void *const *contrib, int layout,
                     const paro_adam_t *hp, float *grad_scratch, double *sumsq_scratch, float *p,
                     float *m, float *v, uint16_t *dst_base, void *stream);

@@ -163,6 +163,19 @@ def reduce_shard(lay: Layout, strategy: str, sched: int, rank: int, contribs, la
     return g, sumsq(g[own:own + L])
 
 
+def range_sumsq(lay: Layout, strategy: str, rank: int, g: np.ndarray) -> float:
+    """Sum of squares over the rank's whole update range (g: the reduced gradient over that
+    range): one sum per chunk, the chunks' sums added in chunk order.  It is the norm a rank can
+    form on its own; where the optimizer state is sharded over all ranks it equals the
+    own-chunk value reduce_shard returns."""
+    ob, ol = state_range(lay, rank, strategy[2])
+    assert g.shape[0] == ol
+    tot = 0.0
+    for lo in range(0, ol, lay.L):
+        tot += sumsq(g[lo:lo + lay.L])
+    return tot
+
+
 def adam_shard(lay: Layout, strategy: str, rank: int, g, p, m, v, *, total_sumsq: float, hp: dict,
                step: int, no_decay: Optional[Sequence[int]] = None, literal32: bool = False) -> float:
     """Clip coefficient from the global sum of squares, then Adam over the update

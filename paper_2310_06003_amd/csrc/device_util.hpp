@@ -61,6 +61,9 @@ namespace {
 #ifndef PARO_FOLD_T_LOADS_PER_CU
 #define PARO_FOLD_T_LOADS_PER_CU 448
 #endif
+#ifndef PARO_MIN_WAVES_PER_CU
+#define PARO_MIN_WAVES_PER_CU 8     // the throttle never goes below this
+#endif
 #ifndef PARO_HOP_WAVES_PER_CU
 #define PARO_HOP_WAVES_PER_CU 0
 #endif

@@ -396,13 +396,14 @@ unsigned throttle_lds(int lds_per_cu, int waves_per_cu) {
     return bytes > 65536u ? 65536u : bytes;
 }
 
-// Waves per compute unit that keep about `loads_per_cu` loads in flight when a wave of the fold
-// issues min(P, PARO_BATCH) + extra loads at a time; 0 (no limit) when that is all that fit anyway.
-int fold_waves(int P, int extra, int loads_per_cu) {
-    const int per_wave = std::min(P, PARO_BATCH) + extra;
+// Waves per compute unit that keep about `loads_per_cu` loads in flight when a wave issues
+// `per_wave` loads at a time; 0 (no limit) when that is all that fit anyway.
+int fold_waves(int per_wave, int loads_per_cu) {
     const int waves = loads_per_cu / per_wave;
-    return waves >= 32 ? 0 : std::max(waves, 8);
+    return waves >= 32 ? 0 : std::max(waves, PARO_MIN_WAVES_PER_CU);
 }
+// Loads a wave of the fold has in flight: a batch of contributions, for each block it takes.
+int fold_loads(int P, int blocks_per_wave = 1) { return std::min(P, PARO_BATCH) * blocks_per_wave; }
 
 // What a launch needs from the device besides the caller's buffers: the LDS size behind the
 // occupancy throttle and the scratch array of partial sums (per-block sums of a sweep-1 launch,
@@ -412,11 +413,14 @@ struct Scratch {
     int lds_per_cu;
     double *partials;
     double *level2;
+    double *chunk_sums;    // [PARO_MAX_RANKS] one sum per chunk of an update range of several chunks
     bool plan_tables;      // the plan's device tables (offset tables, per-tile tables) exist
 };
 
 Scratch plan_scratch(const paro_plan_t *pl) {
-    return Scratch{pl->dev.lds_per_cu, pl->dev.partials, pl->dev.partials + pl->dev.n_partials, true};
+    double *level2 = pl->dev.partials + pl->dev.n_partials;
+    const int64_t n_level2 = (pl->dev.n_partials + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
+    return Scratch{pl->dev.lds_per_cu, pl->dev.partials, level2, level2 + n_level2, true};
 }
 
 template <class T>
@@ -456,7 +460,7 @@ int fill_tables(const paro_plan_t *pl, paro_device_tables &d) {
     if (n_part < PARO_MIN_PARTIALS) n_part = PARO_MIN_PARTIALS;
     d.n_partials = n_part;
     const int64_t n_level2 = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
-    PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), (n_part + n_level2) * sizeof(double)));
+    PARO_HIP(hipMalloc(reinterpret_cast<void **>(&d.partials), (n_part + n_level2 + PARO_MAX_RANKS) * sizeof(double)));
     return PARO_OK;
 }
 
@@ -654,7 +658,7 @@ int launch_reduce(const paro_plan_t *pl, const Scratch &sc, int layout, const Sr
     double *partials = sc.partials;
     if (layout == PARO_CHUNK) {
         const unsigned grid = (piece_grid(n) + 7u) & ~7u;       // a multiple of 8: see partial_slot()
-        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), PARO_FOLD_LOADS_PER_CU));
         PARO_BY_DTYPE(pl->dtype[0], hipLaunchKernelGGL((k_reduce4<DT, SUMSQ>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P,
                                                        group_len, n, g, partials));
         return (int)grid;
@@ -665,16 +669,16 @@ int launch_reduce(const paro_plan_t *pl, const Scratch &sc, int layout, const Sr
     if (pl->P <= PARO_PAIR_MAX_RANKS && (int64_t)piece_grid(n) >= pair_min_blocks) {
         // few contributions, a launch that fills the GPU many times over: two blocks per wave
         const unsigned grid = (piece_grid(n, 2) + 7u) & ~7u;
-        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(2 * pl->P, 0, PARO_FOLD_T_LOADS_PER_CU));
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P, 2), PARO_FOLD_T_LOADS_PER_CU));
         hipLaunchKernelGGL((k_reduce4t<SUMSQ, 2, 8>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials, tm);
         return (int)grid;
     }
     const unsigned grid = (piece_grid(n) + 7u) & ~7u;
     if (pl->P <= PARO_PAIR_MAX_RANKS) {
-        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 0, PARO_FOLD_T_LOADS_PER_CU));
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), PARO_FOLD_T_LOADS_PER_CU));
         hipLaunchKernelGGL((k_reduce4t<SUMSQ, 1, 8>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials, tm);
     } else {
-        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(pl->P, 0, PARO_FOLD_LOADS_PER_CU));
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), PARO_FOLD_LOADS_PER_CU));
         hipLaunchKernelGGL((k_reduce4t<SUMSQ, 1, PARO_BATCH>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g,
                            partials, tm);
     }
@@ -686,7 +690,7 @@ template <bool MASK>
 void launch_fused(const paro_plan_t *pl, const Scratch &sc, int layout, const SrcTable &tab, int group_len, int64_t c,
                   const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
-    const int waves = fold_waves(pl->P, 3, PARO_FUSED_LOADS_PER_CU);
+    const int waves = fold_waves(fold_loads(pl->P) + 3, PARO_FUSED_LOADS_PER_CU);
     const TensorMap tm = map_for(pl, sc, c * pl->L, true);
     const unsigned grid = piece_grid(n), lds = throttle_lds(sc.lds_per_cu, waves);
     if (layout == PARO_TENSORS)
@@ -697,36 +701,49 @@ void launch_fused(const paro_plan_t *pl, const Scratch &sc, int layout, const Sr
                                                        pl->P, group_len, n, a, p, m, v, dst, tm));
 }
 
-// Sweep 1 over the whole update range, chunk by chunk; the sum of squares covers
-// the rank's own chunk only.
+// Adds the n_part partial sums a sweep-1 launch left in the scratch array into *out (device).
+int finalize_partials(const Scratch &sc, int n_part, double *out, hipStream_t st) {
+    if (n_part > 2 * FINALIZE_CHUNK) {       // two levels: slices of 2048 partials, then their sums
+        const int nb = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
+        hipLaunchKernelGGL(k_finalize, dim3(nb), dim3(FINALIZE_TPB), 0, st, sc.partials, n_part, FINALIZE_CHUNK, sc.level2);
+        PARO_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, sc.level2, nb, nb, out);
+    } else {
+        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, sc.partials, n_part, n_part, out);
+    }
+    PARO_HIP(hipGetLastError());
+    return PARO_OK;
+}
+
+// Sweep 1 over the whole update range, chunk by chunk.  The sum of squares covers the rank's own
+// chunk only (so that the ranks' values add up to the model's) - or, with norm_over_range, every
+// chunk of the update range: one sum per chunk, added in chunk order.
 int do_reduce(const paro_plan_t *pl, const Scratch &sc, int rank, const void *const *contrib, int layout, float *grad_out,
-              double *sumsq_out, hipStream_t st) {
+              double *sumsq_out, bool norm_over_range, hipStream_t st) {
+    int rc;
     int64_t ob, on;
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
     const int own = paro::chunk_of_rank(pl, rank);
-    int n_part = 0;                      // partial sums written by the launch over the rank's own chunk
-    for (int64_t c = ob / pl->L; c < (ob + on) / pl->L; ++c) {
+    const int64_t c0 = ob / pl->L, c1 = (ob + on) / pl->L;
+    const bool per_chunk = sumsq_out && norm_over_range && c1 - c0 > 1;
+    for (int64_t c = c0; c < c1; ++c) {
         SrcTable tab;
         int gl;
         const int64_t lo = c * pl->L - ob;
         src_table(pl, (int)c, contrib, layout, lo, &tab, &gl);
-        if (c == own && sumsq_out)
-            n_part = launch_reduce<true>(pl, sc, layout, tab, gl, c, grad_out + lo, st);
-        else
-            launch_reduce<false>(pl, sc, layout, tab, gl, c, grad_out + lo, st);
-        PARO_HIP(hipGetLastError());
-    }
-    if (sumsq_out) {
-        if (n_part > 2 * FINALIZE_CHUNK) {       // two levels: slices of 2048 partials, then their sums
-            const int nb = (n_part + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
-            double *level2 = sc.level2;
-            hipLaunchKernelGGL(k_finalize, dim3(nb), dim3(FINALIZE_TPB), 0, st, sc.partials, n_part, FINALIZE_CHUNK,
-                               level2);
+        if (sumsq_out && (per_chunk || c == own)) {
+            const int n_part = launch_reduce<true>(pl, sc, layout, tab, gl, c, grad_out + lo, st);
             PARO_HIP(hipGetLastError());
-            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, level2, nb, nb, sumsq_out);
+            // the next launch reuses the scratch array: this chunk's partials are added up first
+            if ((rc = finalize_partials(sc, n_part, per_chunk ? sc.chunk_sums + (c - c0) : sumsq_out, st))) return rc;
         } else {
-            hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, sc.partials, n_part, n_part, sumsq_out);
+            launch_reduce<false>(pl, sc, layout, tab, gl, c, grad_out + lo, st);
+            PARO_HIP(hipGetLastError());
         }
+    }
+    if (per_chunk) {
+        const int nc = (int)(c1 - c0);
+        hipLaunchKernelGGL(k_finalize, dim3(1), dim3(FINALIZE_TPB), 0, st, sc.chunk_sums, nc, nc, sumsq_out);
         PARO_HIP(hipGetLastError());
     }
     return PARO_OK;
@@ -770,7 +787,8 @@ int launch_step(const paro_plan_t *pl, const Scratch &sc, int rank, const void *
     paro_pack_slot(pl, rank, &dl, &so, &sl);
     uint16_t *dst = dst_base + so;
     if (a.max_norm > 0.0f || a.skip_nonfinite) {
-        if ((rc = do_reduce(pl, sc, rank, contrib, layout, grad_scratch, sumsq_scratch, st))) return rc;
+        // the norm this rank can form on its own: over everything it updates (its update range)
+        if ((rc = do_reduce(pl, sc, rank, contrib, layout, grad_scratch, sumsq_scratch, true, st))) return rc;
         return do_adam(pl, sc, rank, a, grad_scratch, sumsq_scratch, p, m, v, dst, st);
     }
     paro::letter_range(pl, rank, pl->letters[2], &ob, &on);
@@ -794,7 +812,7 @@ int launch_step(const paro_plan_t *pl, const Scratch &sc, int rank, const void *
 // runs on holds its own copy of this array, at its own address, until the process ends.
 constexpr int64_t STATIC_PARTIALS = PARO_STATIC_MAX_CHUNK / PIECE;
 constexpr int64_t STATIC_LEVEL2 = (STATIC_PARTIALS + FINALIZE_CHUNK - 1) / FINALIZE_CHUNK;
-static __device__ __align__(256) double scratch[STATIC_PARTIALS + STATIC_LEVEL2];
+static __device__ __align__(256) double scratch[STATIC_PARTIALS + STATIC_LEVEL2 + PARO_MAX_RANKS];
 
 constexpr int MAX_DEVICES = 64;
 struct StaticScratch {
@@ -825,7 +843,8 @@ int static_scratch(Scratch *out) {
         g_static.lds_per_cu[dev] = lds;
         g_static.ptr[dev] = ptr;
     }
-    *out = Scratch{g_static.lds_per_cu[dev], g_static.ptr[dev], g_static.ptr[dev] + STATIC_PARTIALS, false};
+    *out = Scratch{g_static.lds_per_cu[dev], g_static.ptr[dev], g_static.ptr[dev] + STATIC_PARTIALS,
+                   g_static.ptr[dev] + STATIC_PARTIALS + STATIC_LEVEL2, false};
     return PARO_OK;
 }
 
@@ -849,7 +868,7 @@ int paro_reduce_shard(paro_plan_t *pl, int rank, const void *const *contrib, int
         return fail(PARO_EALIGN, "paro_reduce_shard: sumsq_out is not 8-byte aligned");
     if ((rc = ensure_device(pl))) return rc;
     if (layout == PARO_TENSORS && (rc = ensure_tile_tables(pl, rank))) return rc;
-    return do_reduce(pl, plan_scratch(pl), rank, contrib, layout, grad_out, sumsq_out, static_cast<hipStream_t>(stream));
+    return do_reduce(pl, plan_scratch(pl), rank, contrib, layout, grad_out, sumsq_out, false, static_cast<hipStream_t>(stream));
 }
 
 int paro_adam_shard(paro_plan_t *pl, int rank, const paro_adam_t *hp, const float *grad, const double *total_sumsq,

@@ -111,7 +111,11 @@ def run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, step, r
     assert abs(float(ss.item()) - ss_ref) <= 1e-12 * ss_ref, what
 
     p0, m0, v0 = (a[ob:ob + ol].copy() for a in state)
-    total = ss_ref
+    # the fused step forms its norm over the rank's whole update range (= the own-chunk value where the
+    # optimizer state is sharded over all ranks); the split calls below are handed the same total
+    total = orc.range_sumsq(lay, strategy, rank, g_ref)
+    if strategy[2] == "G":
+        assert total == ss_ref
     ref = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=step)
     lit = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=step, literal32=True)
     g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
@@ -136,7 +140,7 @@ def run_rank(paro, pl, lay, strategy, sched, rank, dev, host, state, hp, step, r
     assert (fused["q"] == orc.bf16_rne(fused["p"])).all(), what + ": pack is not the rounding of the stored p"
     assert not q_all[:slot_off].any() and not q_all[slot_off + slot_len:].any(), what + ": wrote outside the slot"
     if hp["max_norm"] > 0:
-        assert np_of(gs).tobytes() == g_ref.tobytes() and abs(float(ss2.item()) - ss_ref) <= 1e-12 * ss_ref
+        assert np_of(gs).tobytes() == g_ref.tobytes() and abs(float(ss2.item()) - total) <= 1e-12 * total
 
     if check_unfused:
         p, m, v = fresh()

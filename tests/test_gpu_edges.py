@@ -81,7 +81,8 @@ def _tensor_rank(paro, pl, lay, strategy, sched, rank, tables, host, state, hp, 
     """One rank, tensor layout: fused step against the oracle (reduced gradient and sum of
     squares when the step stores them)."""
     ob, ol = orc.state_range(lay, rank, strategy[2])
-    g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, host, "tensors")
+    g_ref, _own = orc.reduce_shard(lay, strategy, sched, rank, host, "tensors")
+    ss_ref = orc.range_sumsq(lay, strategy, rank, g_ref)          # the fused step's norm: over the whole update range
     old = [a[ob:ob + ol].copy() for a in state]
     ref = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=step, no_decay=no_decay)
     lit = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=step, no_decay=no_decay,

@@ -85,6 +85,41 @@ def test_overflowed_gradient_skips_the_step(paro, poison):
     assert not np.isfinite(got2["p"]).all()
 
 
+@pytest.mark.parametrize("strategy", ["III", "NNN"])
+def test_overflow_outside_the_own_chunk_skips_every_replica(paro, strategy):
+    """Optimizer state sharded inside the group only / not at all: a rank updates chunks that other
+    ranks own.  The fused step's norm covers the whole update range, so an overflowed gradient in
+    ANY chunk of it skips the step, and every rank that holds a replica of that chunk skips alike
+    (with the norm of the own chunk alone the replicas would part ways)."""
+    P, G = 4, 2
+    lay, pl, dev, state = _setup(paro, P, G, strategy, P * 8 * 600, seed=6)
+    victim = 2 * lay.L + 77                          # flat index inside chunk 2 (owner: rank 1)
+    dev[3][victim] = float("inf")
+    hp = hp_dict(P, max_norm=0.0, grad_scale=1.0 / (P * LOSS_SCALE), skip_nonfinite=True)
+    sched = orc.default_sched(P, G)
+    for rank in range(P):
+        ob, ol = orc.state_range(lay, rank, strategy[2])
+        covers = ob <= victim < ob + ol
+        got, (p0, m0, v0), host, _ = _step(paro, pl, lay, strategy, rank, dev, state, hp, 1)
+        g_ref, own_ss = orc.reduce_shard(lay, strategy, sched, rank, host, "chunk")
+        total = orc.range_sumsq(lay, strategy, rank, g_ref)
+        ref = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=1, fmt="f16")
+        if covers:
+            assert not np.isfinite(got["ss"]) and not np.isfinite(total)
+            if orc.chunk_of_rank(rank, P, G) != 2:
+                assert np.isfinite(own_ss), "the rank's own chunk is clean: only the range-wide norm sees the overflow"
+            for k, old in (("p", p0), ("m", m0), ("v", v0)):
+                assert got[k].tobytes() == old.tobytes() == ref[k].tobytes(), (rank, k)
+            assert (got["q_all"] == np.float16(3.0).view(np.uint16)).all()
+        else:
+            assert np.isfinite(got["ss"]) and abs(got["ss"] - total) <= 1e-12 * total
+            lit = oracle_update(lay, strategy, rank, g_ref, p0, m0, v0, total_sumsq=total, hp=hp, step=1, fmt="f16",
+                                literal32=True)
+            g_hat = float(np.float32(hp["grad_scale"])) * g_ref.astype(np.float64)
+            compare_step(got, ref, p_old=p0, m_old=m0, g_hat=g_hat, what=f"{strategy} rank {rank}", literal=lit, fmt="f16")
+    assert strategy != "NNN" or all(orc.state_range(lay, r, "N")[1] == P * lay.L for r in range(P))
+
+
 def test_tensor_layout_with_three_dtypes(paro):
     rng = np.random.default_rng(9)
     sizes = [int(s) for s in rng.integers(0, 12, 30)] + [4100, 1, 9000, 2047, 6, 3000]

@@ -83,6 +83,7 @@ def test_random_configuration(paro, seed, monkeypatch):
         else:
             g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, [h[ob:ob + ol] for h in host], "chunk")
             ptrs, kind = [t[ob:ob + ol].data_ptr() for t in dev], paro.PARO_CHUNK
+        ss_ref = orc.range_sumsq(lay, strategy, rank, g_ref)      # the fused step's norm: over the whole update range
         old = [a[ob:ob + ol].copy() for a in state]
         ref = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=c["step"], no_decay=no_decay)
         lit = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=c["step"],

@@ -237,7 +237,8 @@ def test_tensor_layout_small_ragged(paro, table, monkeypatch):
                 host = [[np_of(t) for t in s.tensors] for s in sets]
                 for rank in range(P):
                     ob, ol = orc.state_range(lay, rank, strategy[2])
-                    g_ref, ss_ref = orc.reduce_shard(lay, strategy, sched, rank, host, "tensors")
+                    g_ref, _own = orc.reduce_shard(lay, strategy, sched, rank, host, "tensors")
+                    ss_ref = orc.range_sumsq(lay, strategy, rank, g_ref)      # the fused step's norm
                     old = ora_state[rank]
                     ref = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=ss_ref, hp=hp, step=step,
                                         no_decay=no_decay)

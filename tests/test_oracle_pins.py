@@ -201,6 +201,27 @@ def test_reduce_shard_chunk_layout_brute_force(P, G, strategy):
     assert norm_total == float(np.sum(direct ** 2))
 
 
+def test_range_sumsq_is_the_exact_sum_over_the_update_range():
+    """The norm the fused step forms on one rank: all of the rank's update range, against math.fsum;
+    equal to reduce_shard's own-chunk value exactly where the range is one chunk."""
+    import math
+    P, G = 6, 3
+    lay = orc.layout(P, G, [1000, 37, 4000])
+    rng = np.random.default_rng(3)
+    for strategy in ("GGG", "IIG", "III", "NNI", "NNN"):
+        for rank in (0, 4):
+            ob, ol = orc.state_range(lay, rank, strategy[2])
+            contribs = [(rng.standard_normal(ol) * 1e-2).astype(np.float32) for _ in range(P)]
+            g, own = orc.reduce_shard(lay, strategy, orc.default_sched(P, G), rank, contribs, "chunk")
+            tot = orc.range_sumsq(lay, strategy, rank, g)
+            exact = math.fsum(float(x) * float(x) for x in g)
+            assert abs(tot - exact) <= 1e-14 * exact
+            if strategy[2] == "G":
+                assert tot == own
+            else:
+                assert tot > own * 1.5
+
+
 # ---- the tolerance checker itself: planted errors must be caught ------------------------------------
 def _one_step(n=20_000, seed=7):
     g = _rand(n, seed, 1e-3)
