@@ -308,3 +308,66 @@ def test_update_range_of_several_chunks_at_size(paro, strategy, ranks):
         for max_norm in (0.5, 0.0):
             _tensor_rank(paro, plm, lay, strategy, sched, rank, tables, host_t, state, hp_dict(P, max_norm=max_norm), 1,
                          no_decay=no_decay, what=f"multi-chunk clip{max_norm}")
+
+
+@pytest.mark.parametrize("mode", ["per-block table", "search", "two blocks per wave"])
+def test_blocks_holding_hundreds_of_tensors(paro, mode, monkeypatch):
+    """Runs of one- to three-element tensors: blocks of 256 elements that hold up to 256 tensors.  A block
+    finds its elements' tensors with one table entry per lane (64 segment starts) and falls back to a
+    per-lane search through the table when more than 64 tensors start inside it - both happen here, next
+    to ordinary blocks, with mixed dtypes and a decay mask, in the tensor layout and (for the mask) the
+    chunk layout."""
+    if mode == "search":
+        monkeypatch.setenv("PARO_TILE_TABLE_MAX_TILES", "0")
+    if mode == "two blocks per wave":
+        monkeypatch.setenv("PARO_PAIR_MIN_BLOCKS", "0")
+    rng = np.random.default_rng(77)
+    sizes = ([1] * 300 + [5000] + [int(x) for x in rng.integers(1, 4, 400)] + [700, 0, 0, 3] + [2] * 90 + [4096]
+             + [int(x) for x in rng.integers(1, 9, 200)] + [1] * 70 + [9])
+    dtypes = [int(x) for x in rng.integers(0, 3, len(sizes))]
+    no_decay = [int(x) for x in rng.integers(0, 2, len(sizes))]
+    P, G = 4, 2
+    lay = orc.layout(P, G, sizes)
+    starts = np.cumsum([0] + sizes[:-1])[np.array(sizes) > 0]
+    per_block = np.bincount(starts // 256)
+    assert per_block.max() > 200 and (per_block > 64).sum() >= 2 and ((per_block > 1) & (per_block <= 64)).sum() >= 2
+    n = P * lay.L
+    state = [np_of(t) for t in wl.master_state(n, 78)]
+    for a in state:
+        a[lay.total:] = 0
+    sets = wl.tensor_contribs(P, sizes, dtypes, 79, 1, device=DEV, align_elems=1)
+    tables = [PtrTable(s.tensors) for s in sets]
+    host_t = [[np_of(t) for t in s.tensors] for s in sets]
+    dev, host = flat_inputs(P, n, seed=80)
+    for t, h in zip(dev, host):
+        t[lay.total:] = 0
+        h[lay.total:] = 0
+    for strategy in ("IIG", "III"):
+        sched = orc.default_sched(P, G)
+        plm = paro.paro_plan(P, G, strategy, sizes, grad_dtype=dtypes, no_decay=no_decay)
+        plc = paro.paro_plan(P, G, strategy, sizes, no_decay=no_decay)          # chunk layout: one dtype
+        for rank in range(P):
+            for max_norm in (0.01, 0.0):
+                hp = dict(hp_dict(P, max_norm=max_norm), weight_decay=0.1)
+                _tensor_rank(paro, plm, lay, strategy, sched, rank, tables, host_t, state, hp, 3, no_decay=no_decay,
+                             what=f"tiny tensors, {mode}, clip {max_norm}")
+            # chunk layout with the mask: sweep 2 / the single sweep look the tensors up for the decay flag only
+            ob, ol = orc.state_range(lay, rank, strategy[2])
+            g_ref, _ = orc.reduce_shard(lay, strategy, sched, rank, [h[ob:ob + ol] for h in host], "chunk")
+            hp = dict(hp_dict(P, max_norm=0.01), weight_decay=0.1)
+            total = orc.range_sumsq(lay, strategy, rank, g_ref)
+            old = [a[ob:ob + ol].copy() for a in state]
+            ref = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=total, hp=hp, step=3, no_decay=no_decay)
+            lit = oracle_update(lay, strategy, rank, g_ref, *old, total_sumsq=total, hp=hp, step=3, no_decay=no_decay,
+                                literal32=True)
+            p, m, v = (torch.from_numpy(a.copy()).to(DEV) for a in old)
+            dst_len, slot_off, slot_len = orc.pack_slot(lay, rank, strategy)
+            dst = torch.zeros(dst_len, dtype=torch.bfloat16, device=DEV)
+            gs = torch.empty(ol, dtype=torch.float32, device=DEV)
+            ss = torch.zeros(1, dtype=torch.float64, device=DEV)
+            paro.paro_step_fused(plc, rank, [t[ob:ob + ol].data_ptr() for t in dev], paro.PARO_CHUNK, hp_struct(paro, hp, 3),
+                                 gs.data_ptr(), ss.data_ptr(), p.data_ptr(), m.data_ptr(), v.data_ptr(), dst.data_ptr(), stream())
+            got = dict(p=np_of(p), m=np_of(m), v=np_of(v), q=np_of(dst)[slot_off:slot_off + slot_len])
+            g_hat = float(np.float32(hp["grad_scale"])) * ref["coef"] * g_ref.astype(np.float64)
+            compare_step(got, ref, p_old=old[0], m_old=old[1], g_hat=g_hat, what=f"tiny tensors, chunk + mask, rank {rank}",
+                         literal=lit)
