@@ -61,6 +61,19 @@ namespace {
 #ifndef PARO_FOLD_T_LOADS_PER_CU
 #define PARO_FOLD_T_LOADS_PER_CU 448
 #endif
+// ... with more contributions than that: a list of few large tensors behaves like the chunk layout
+// (its look-ups hit the scalar cache) and keeps the chunk layout's budget; a list of many small
+// tensors wants every wave it can get.  "Large": at least this many blocks per tensor piece in the
+// chunk, on average.
+#ifndef PARO_DENSE_BLOCKS_PER_TENSOR
+#define PARO_DENSE_BLOCKS_PER_TENSOR 1024
+#endif
+#ifndef PARO_FOLD_TM_LOADS_PER_CU
+#define PARO_FOLD_TM_LOADS_PER_CU 100000
+#endif
+#ifndef PARO_FUSED_T_LOADS_PER_CU      // the single sweep over many small tensors
+#define PARO_FUSED_T_LOADS_PER_CU 100000
+#endif
 #ifndef PARO_MIN_WAVES_PER_CU
 #define PARO_MIN_WAVES_PER_CU 8     // the throttle never goes below this
 #endif

@@ -650,6 +650,17 @@ void src_table(const paro_plan_t *pl, int chunk, const void *const *contrib, int
         }                                  \
     } while (0)
 
+// Whether chunk c is cut into many small pieces of tensors (fewer than PARO_DENSE_BLOCKS_PER_TENSOR
+// blocks per piece on average) rather than a few large ones.
+bool many_small_tensors(const paro_plan_t *pl, int64_t c) {
+    const int64_t f0 = c * pl->L, f1 = std::min((c + 1) * pl->L, pl->total);
+    if (f0 >= f1) return false;                                             // all padding
+    const auto first = std::upper_bound(pl->nz_off.begin(), pl->nz_off.end(), f0) - 1;
+    const auto last = std::lower_bound(pl->nz_off.begin(), pl->nz_off.end(), f1);
+    const int64_t pieces = last - first;
+    return (int64_t)piece_grid(pl->L) < pieces * PARO_DENSE_BLOCKS_PER_TENSOR;
+}
+
 // Launches sweep 1 over chunk c; returns the number of per-block partial sums it writes.
 template <bool SUMSQ>
 int launch_reduce(const paro_plan_t *pl, const Scratch &sc, int layout, const SrcTable &tab, int group_len, int64_t c,
@@ -678,7 +689,8 @@ int launch_reduce(const paro_plan_t *pl, const Scratch &sc, int layout, const Sr
         const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), PARO_FOLD_T_LOADS_PER_CU));
         hipLaunchKernelGGL((k_reduce4t<SUMSQ, 1, 8>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials, tm);
     } else {
-        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), PARO_FOLD_LOADS_PER_CU));
+        const int budget = many_small_tensors(pl, c) ? PARO_FOLD_TM_LOADS_PER_CU : PARO_FOLD_LOADS_PER_CU;
+        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), budget));
         hipLaunchKernelGGL((k_reduce4t<SUMSQ, 1, PARO_BATCH>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g,
                            partials, tm);
     }
@@ -690,7 +702,8 @@ template <bool MASK>
 void launch_fused(const paro_plan_t *pl, const Scratch &sc, int layout, const SrcTable &tab, int group_len, int64_t c,
                   const AdamConsts &a, float *p, float *m, float *v, uint16_t *dst, hipStream_t st) {
     const int64_t n = pl->L;
-    const int waves = fold_waves(fold_loads(pl->P) + 3, PARO_FUSED_LOADS_PER_CU);
+    const bool small = layout == PARO_TENSORS && many_small_tensors(pl, c);
+    const int waves = fold_waves(fold_loads(pl->P) + 3, small ? PARO_FUSED_T_LOADS_PER_CU : PARO_FUSED_LOADS_PER_CU);
     const TensorMap tm = map_for(pl, sc, c * pl->L, true);
     const unsigned grid = piece_grid(n), lds = throttle_lds(sc.lds_per_cu, waves);
     if (layout == PARO_TENSORS)

@@ -177,7 +177,7 @@ __device__ __forceinline__ void locate4(const TensorMap &tm, int seg, int64_t f0
 // in the chunk layout; else element loads.  The test is wave-uniform, source by source.
 template <int DT, int KB = PARO_BATCH>
 struct Tensor4Loader {
-    static constexpr int kBatch = KB;
+    static constexpr int kBatch = (DT == PARO_F32 && KB > 8) ? KB / 2 : KB;     // 32 registers of loads in flight at most
     static constexpr int kElems = 4;
     static constexpr int ESIZE = DT == PARO_F32 ? 4 : 2;
     using Raw = typename Chunk4Loader<DT>::Raw;
