@@ -84,10 +84,10 @@ namespace {
 #define PARO_COPY_WAVES_PER_CU 0
 #endif
 
-constexpr int WAVE = 64;              // a wave handles one piece of a sweep; most kernels run in one-wave blocks
+constexpr int WAVE = 64;              // threads of a block: every sweep kernel runs in one-wave blocks
 constexpr int EPT = 4;                // elements per thread
 constexpr int PIECE = WAVE * EPT;     // elements per block
-constexpr int TILE = PARO_TILE;       // granularity of the plan's per-tile table
+constexpr int TILE = PARO_TILE;       // granularity of the plan's per-block table
 constexpr int FINALIZE_TPB = 256;     // threads of the kernel that adds the partial sums
 constexpr int FINALIZE_CHUNK = 2048;  // partials per block in its first level
 static_assert(TILE == PIECE, "the per-tile table has one entry per block");

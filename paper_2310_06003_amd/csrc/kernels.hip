@@ -15,7 +15,10 @@
 //             beaten persistent grid-stride blocks by 8-15 %.
 //   occupancy the heavy sweeps ask for unused dynamic LDS so that only 10-14 waves
 //             run per compute unit: fewer requests outstanding fight less over
-//             DRAM pages (another 3-6 %).
+//             DRAM pages (another 3-6 %).  The tensor layout over many small
+//             tensors wants the opposite - its waves wait on look-ups with no
+//             data in flight - and gets two blocks per wave (few contributions)
+//             or every wave the registers allow.
 //   caches    everything is touched once: streaming (non-temporal) loads; stores
 //             through per-wave buffer descriptors, which let the instruction say
 //             "streaming, system scope" (nt sc1: 2 % better than nt alone).
@@ -26,9 +29,10 @@
 //             -> one partial per block -> a small kernel adds the partials in a
 //             fixed order, in two levels.  No atomics: run-to-run identical.
 //   tensors   the tensor layout and the weight-decay mask need the tensor an
-//             element belongs to: a per-tile table (built once per chunk) answers
-//             for blocks inside one tensor with a single look-up; blocks with a
-//             tensor boundary inside search the offset table lane by lane.
+//             element belongs to: a per-block table (built once per chunk) answers
+//             with a single look-up; a block with a tensor boundary inside finds
+//             its elements' tensors with one load per lane and a search across
+//             the lanes' registers.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
