@@ -10,11 +10,11 @@ from harness import DEV, PtrTable, hp_dict, hp_struct, np_of
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("layout", ["chunk", "tensors with a decay mask"])
+@pytest.mark.parametrize("layout", ["chunk", "chunk, the entry point that allocates nothing", "tensors with a decay mask"])
 @pytest.mark.parametrize("max_norm", [0.0, 0.01])
 def test_fused_step_replays_from_a_graph(paro, max_norm, layout):
     P, G, strategy, rank = 8, 4, "IIG", 3
-    if layout == "chunk":
+    if layout.startswith("chunk"):
         sizes = [P * 2048 * 40 + 24]
         pl = paro.paro_plan(P, G, strategy, sizes)
         L = paro.paro_shard_len(pl)
@@ -40,8 +40,12 @@ def test_fused_step_replays_from_a_graph(paro, max_norm, layout):
                     ss=torch.zeros(1, dtype=torch.float64, device=DEV))
 
     def step(s, stream):
-        paro.paro_step_fused(pl, rank, ptrs, kind, hs, s["g"].data_ptr(), s["ss"].data_ptr(),
-                             s["p"].data_ptr(), s["m"].data_ptr(), s["v"].data_ptr(), s["dst"].data_ptr(), stream)
+        if "allocates nothing" in layout:       # its plan never makes a device call of the allocating kind
+            paro.paro_step_fused_static(pl, rank, ptrs, hs, s["g"].data_ptr(), s["ss"].data_ptr(),
+                                        s["p"].data_ptr(), s["m"].data_ptr(), s["v"].data_ptr(), s["dst"].data_ptr(), stream)
+        else:
+            paro.paro_step_fused(pl, rank, ptrs, kind, hs, s["g"].data_ptr(), s["ss"].data_ptr(),
+                                 s["p"].data_ptr(), s["m"].data_ptr(), s["v"].data_ptr(), s["dst"].data_ptr(), stream)
 
     # eager: three steps in a row, the state after each kept
     eager = state()
