@@ -121,40 +121,32 @@ void orc_adam64(int64_t n, const float *g, float *p, float *m, float *v, double 
     }
 }
 
-/* ---- Adam, fp32 literal: every operation rounded to fp32, in this order ------
- * Scalars that do not depend on the element are formed in fp64 from the fp32
+/* ---- Adam, all in fp32: the same formulas with every operation rounded to fp32 ------
+ * C evaluates a float expression operation by operation in float (FLT_EVAL_METHOD 0 on this
+ * target) and the build forbids fusing a multiply into an add, so each line below is the
+ * sequence of IEEE fp32 operations it spells: scale; [L2 term;] the two moving averages;
+ * square root, division by sqrt(1 - b2^t), + eps; division; times lr / (1 - b1^t); decay and
+ * subtraction.  Scalars that do not depend on the element are formed in fp64 from the fp32
  * hyper-parameters and rounded to fp32 once. */
 void orc_adam32(int64_t n, const float *g, float *p, float *m, float *v, double sc_d, float lr,
                 float beta1, float beta2, float eps, float wd, int step, int adamw) {
     const float sc = (float)sc_d;
-    const float omb1 = (float)(1.0 - (double)beta1), omb2 = (float)(1.0 - (double)beta2);
-    const float bc1 = (float)(1.0 - pow((double)beta1, (double)step));
-    const float bc2 = (float)(1.0 - pow((double)beta2, (double)step));
-    const float step_size = (float)((double)lr / (double)bc1);
-    const float sqrt_bc2 = (float)sqrt((double)bc2);
-    const float decay = (float)(1.0 - (double)lr * (double)wd);
+    const float one_minus_b1 = (float)(1.0 - (double)beta1), one_minus_b2 = (float)(1.0 - (double)beta2);
+    const float bias1 = (float)(1.0 - pow((double)beta1, (double)step));
+    const float bias2 = (float)(1.0 - pow((double)beta2, (double)step));
+    const float lr_over_bias1 = (float)((double)lr / (double)bias1);
+    const float root_bias2 = (float)sqrt((double)bias2);
+    const float keep = (float)(1.0 - (double)lr * (double)wd);
 #pragma omp parallel for schedule(static)
     for (int64_t e = 0; e < n; e++) {
-        float gh = sc * g[e], pe = p[e];
-        if (!adamw) gh = gh + wd * pe;
-        float t1 = beta1 * m[e], t2 = omb1 * gh;
-        float me = t1 + t2;
-        float t3 = beta2 * v[e], t4 = gh * gh;
-        float t5 = omb2 * t4;
-        float ve = t3 + t5;
-        float den = sqrtf(ve) / sqrt_bc2;
-        den = den + eps;
-        float q = me / den;
-        float upd = step_size * q;
-        if (adamw) {
-            float pd = pe * decay;
-            pe = pd - upd;
-        } else {
-            pe = pe - upd;
-        }
-        m[e] = me;
-        v[e] = ve;
-        p[e] = pe;
+        float grad = sc * g[e];
+        if (!adamw) grad = grad + wd * p[e];
+        const float m_new = beta1 * m[e] + one_minus_b1 * grad;
+        const float v_new = beta2 * v[e] + one_minus_b2 * (grad * grad);
+        const float step_e = lr_over_bias1 * (m_new / (sqrtf(v_new) / root_bias2 + eps));
+        p[e] = adamw ? p[e] * keep - step_e : p[e] - step_e;
+        m[e] = m_new;
+        v[e] = v_new;
     }
 }
 
