@@ -49,14 +49,14 @@ namespace {
 #define PARO_ADAM_MASK_WAVES_PER_CU 16   // with a decay mask: a table look-up per wave to hide as well
 #endif
 // Sweep 1 in the tensor layout lets a wave take two consecutive blocks when there are at most this
-// many contributions and the launch has at least that many blocks (see k_reduce4t; a small launch
+// many contributions and the launch has at least that many blocks (see k_reduce4t; the two shapes cross near 50 M elements: a smaller launch
 // wants as many waves as it can get).  Its budget of loads in flight is larger than the chunk
 // layout's: its waves spend part of their life on look-ups, with no data in flight.
 #ifndef PARO_PAIR_MAX_RANKS
 #define PARO_PAIR_MAX_RANKS 8
 #endif
 #ifndef PARO_PAIR_MIN_BLOCKS
-#define PARO_PAIR_MIN_BLOCKS 131072
+#define PARO_PAIR_MIN_BLOCKS 196608
 #endif
 #ifndef PARO_FOLD_T_LOADS_PER_CU
 #define PARO_FOLD_T_LOADS_PER_CU 448

@@ -2,7 +2,7 @@
 list (empty, tiny, tile-sized and large tensors), gradient dtypes, weight-decay mask, layout,
 alignment of the per-tensor gradients, clipping, decay style, with and without the per-tile
 table, with sweep 1's two-blocks-per-wave shape forced on (it is otherwise kept for launches of
-131 072 blocks and more).  Every rank of every configuration, fused entry point, full parity."""
+196 608 blocks and more).  Every rank of every configuration, fused entry point, full parity."""
 import numpy as np
 import pytest
 import torch
