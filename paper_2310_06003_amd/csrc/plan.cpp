@@ -209,9 +209,9 @@ int paro_plan(int P, int G, const char *strategy, const int64_t *tensor_sizes, i
     return PARO_OK;
 }
 
-int64_t paro_total(const paro_plan_t *pl) { return pl ? pl->total : PARO_EINVAL; }
-int64_t paro_shard_len(const paro_plan_t *pl) { return pl ? pl->L : PARO_EINVAL; }
-int64_t paro_padded_total(const paro_plan_t *pl) { return pl ? (int64_t)pl->P * pl->L : PARO_EINVAL; }
+int64_t paro_total(const paro_plan_t *pl) { return pl ? pl->total : (int64_t)PARO_EINVAL; }
+int64_t paro_shard_len(const paro_plan_t *pl) { return pl ? pl->L : (int64_t)PARO_EINVAL; }
+int64_t paro_padded_total(const paro_plan_t *pl) { return pl ? (int64_t)pl->P * pl->L : (int64_t)PARO_EINVAL; }
 int paro_sched(const paro_plan_t *pl) { return pl ? pl->sched : PARO_EINVAL; }
 
 int paro_chunk_of_rank(const paro_plan_t *pl, int rank) {
