@@ -54,8 +54,9 @@
  * range (16 bytes per 256 elements, built when the chunk has at most 4 Mi
  * tiles, or at most PARO_TILE_TABLE_MAX_TILES when that environment variable
  * is set; without it the kernels search; PARO_PAIR_MIN_BLOCKS, also read at
- * every call, overrides from how many blocks on sweep 1 of the tensor layout
- * lets a wave take two blocks - both exist for tests).  Those first calls allocate and copy
+ * every call, makes sweep 1 of the tensor layout give a wave two blocks from
+ * that many blocks on, whatever the tensor list, instead of from the built-in
+ * size on for lists of many small tensors - both exist for tests).  Those first calls allocate and copy
  * synchronously - make them outside any stream capture; every later call only
  * enqueues kernels and can be captured.  Device
  * functions only enqueue work on `stream` (a hipStream_t passed as void*; NULL =

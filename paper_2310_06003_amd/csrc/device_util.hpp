@@ -48,10 +48,14 @@ namespace {
 #ifndef PARO_ADAM_MASK_WAVES_PER_CU
 #define PARO_ADAM_MASK_WAVES_PER_CU 16   // with a decay mask: a table look-up per wave to hide as well
 #endif
-// Sweep 1 in the tensor layout lets a wave take two consecutive blocks when there are at most this
-// many contributions and the launch has at least that many blocks (see k_reduce4t; the two shapes cross near 50 M elements: a smaller launch
-// wants as many waves as it can get).  Its budget of loads in flight is larger than the chunk
-// layout's: its waves spend part of their life on look-ups, with no data in flight.
+// Sweep 1 in the tensor layout.  What decides is the list: a chunk made of a few large tensors
+// ("large": at least PARO_DENSE_BLOCKS_PER_TENSOR blocks per tensor piece in the chunk, on average)
+// behaves like the chunk layout - its look-ups hit the scalar cache - and keeps the chunk layout's
+// shape and budget.  A chunk cut into many small pieces has waves that spend part of their life on
+// look-ups with no data in flight: it is launched without the throttle, and with at most
+// PARO_PAIR_MAX_RANKS contributions and at least PARO_PAIR_MIN_BLOCKS blocks a wave takes two
+// consecutive blocks under a budget twice the chunk layout's (see k_reduce4t; the two shapes cross
+// near 50 M elements: a smaller launch wants as many waves as it can get).
 #ifndef PARO_PAIR_MAX_RANKS
 #define PARO_PAIR_MAX_RANKS 8
 #endif
@@ -61,10 +65,6 @@ namespace {
 #ifndef PARO_FOLD_T_LOADS_PER_CU
 #define PARO_FOLD_T_LOADS_PER_CU 448
 #endif
-// ... with more contributions than that: a list of few large tensors behaves like the chunk layout
-// (its look-ups hit the scalar cache) and keeps the chunk layout's budget; a list of many small
-// tensors wants every wave it can get.  "Large": at least this many blocks per tensor piece in the
-// chunk, on average.
 #ifndef PARO_DENSE_BLOCKS_PER_TENSOR
 #define PARO_DENSE_BLOCKS_PER_TENSOR 1024
 #endif

@@ -679,25 +679,31 @@ int launch_reduce(const paro_plan_t *pl, const Scratch &sc, int layout, const Sr
         return (int)grid;
     }
     const TensorMap tm = map_for(pl, sc, c * pl->L, true);
+    // What decides is the list.  A chunk cut into many small pieces of tensors: its waves wait for their look-ups
+    // with no data in flight, and want more bytes in flight per wave and per compute unit (no throttle; with few
+    // contributions and a launch that fills the GPU many times over, two blocks per wave).  A few large tensors:
+    // the look-ups hit the scalar cache and the launch behaves like the chunk layout's, budget included; only with
+    // 4 contributions or fewer does a wave with one block have too little in flight beside its look-ups.
+    const bool small = many_small_tensors(pl, c);
     int64_t pair_min_blocks = PARO_PAIR_MIN_BLOCKS;
-    if (const char *env = std::getenv("PARO_PAIR_MIN_BLOCKS")) pair_min_blocks = std::atoll(env);     // for tests
-    if (pl->P <= PARO_PAIR_MAX_RANKS && (int64_t)piece_grid(n) >= pair_min_blocks) {
-        // few contributions, a launch that fills the GPU many times over: two blocks per wave
+    const char *env = std::getenv("PARO_PAIR_MIN_BLOCKS");                  // for tests: pairs on any list from this size on
+    if (env) pair_min_blocks = std::atoll(env);
+    if (pl->P <= PARO_PAIR_MAX_RANKS && (small || env || 2 * pl->P <= PARO_PAIR_MAX_RANKS) &&
+        (int64_t)piece_grid(n) >= pair_min_blocks) {
         const unsigned grid = (piece_grid(n, 2) + 7u) & ~7u;
-        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P, 2), PARO_FOLD_T_LOADS_PER_CU));
+        const unsigned lds = throttle_lds(
+            sc.lds_per_cu, fold_waves(fold_loads(pl->P, 2), small ? PARO_FOLD_T_LOADS_PER_CU : PARO_FOLD_LOADS_PER_CU));
         hipLaunchKernelGGL((k_reduce4t<SUMSQ, 2, 8>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials, tm);
         return (int)grid;
     }
     const unsigned grid = (piece_grid(n) + 7u) & ~7u;
-    if (pl->P <= PARO_PAIR_MAX_RANKS) {
-        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), PARO_FOLD_T_LOADS_PER_CU));
+    const unsigned lds =
+        throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), small ? PARO_FOLD_TM_LOADS_PER_CU : PARO_FOLD_LOADS_PER_CU));
+    if (pl->P <= PARO_PAIR_MAX_RANKS)                                       // a batch of 8 contributions: fewer registers
         hipLaunchKernelGGL((k_reduce4t<SUMSQ, 1, 8>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g, partials, tm);
-    } else {
-        const int budget = many_small_tensors(pl, c) ? PARO_FOLD_TM_LOADS_PER_CU : PARO_FOLD_LOADS_PER_CU;
-        const unsigned lds = throttle_lds(sc.lds_per_cu, fold_waves(fold_loads(pl->P), budget));
+    else
         hipLaunchKernelGGL((k_reduce4t<SUMSQ, 1, PARO_BATCH>), dim3(grid), dim3(WAVE), lds, st, tab, pl->P, group_len, n, g,
                            partials, tm);
-    }
     return (int)grid;
 }
 
