@@ -193,7 +193,7 @@ __device__ __forceinline__ void reduce_piece_t(const TensorMap &tm, const Piece 
     }
 }
 
-// A wave takes PPW consecutive blocks.  PPW = 2 is for few contributions (P <= 8): where both
+// A wave takes PPW consecutive blocks.  PPW = 2 is for few contributions (P <= 8) over many small tensors: where both
 // blocks lie inside one tensor - the usual case - the wave folds them as one stream of 512
 // elements per contribution: one look-up and twice the bytes in flight per wave; the cache line
 // that the two blocks share (a block does not start on a line inside its tensor) is fetched once.
