@@ -225,7 +225,7 @@ def main():
     dom_ms = ms1
     achieved = bytes_dom / (dom_ms * 1e-3) / 1e9
     dom_kernel = ("k_reduce4t" if args.layout == "tensors" else "k_reduce4") if clip else "k_fused4"
-    traffic, traffic_source = measured_traffic(args.workload, dom_kernel) if args.layout == "chunk" else (None, None)
+    traffic, traffic_source = measured_traffic(args.workload, dom_kernel)      # summaries are per kernel and workload
     out = {
         "metric": "shard_params_updated_per_s (fused reduce+Adam+pack step)",
         "value": L / (ms_step * 1e-3),
